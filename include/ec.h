@@ -1,0 +1,185 @@
+/*
+ * libelastic_cache -- C ABI of the Elastic Cache hot path on AMD MI355X (gfx950).
+ *
+ * The library implements, as hand-written HIP kernels, the per-layer KV-cache
+ * compression of the paper's instruction-encoding stage and the attention +
+ * fixed-point elimination of its output-generation stage (Sec. 3.3 "One
+ * Sequence, Two Policies"; Alg. 1).
+ *
+ * Conventions common to every entry point
+ *  - Pointers named below as DEVICE point to memory of the current HIP device,
+ *    owned by the caller for the whole call and until the stream has drained.
+ *    The library allocates nothing and frees nothing; scratch comes from the
+ *    caller's workspace `ws` (size from ec_workspace_bytes).
+ *  - All tensors are dense, row-major, in the element type `dt` unless a C type
+ *    is given.  Prompt tensors are [B,H,T,D] (sequence on axis 2, as Alg. 1
+ *    reads it), caches are [B,H,cap,D].  Positions are 0-based.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Work is enqueued asynchronously; no call synchronises with the device.
+ *  - Every entry point returns an ec_status.  Arguments are validated on the
+ *    host before anything is launched: on EC_EINVAL / EC_EUNSUPPORTED /
+ *    EC_EWORKSPACE nothing was enqueued.  EC_EDEVICE reports a HIP launch error.
+ *  - G is the number of score groups per layer: G = 1 is the paper's layer-wise
+ *    policy (all heads of a layer share anchor positions, Sec. 3.3), G = H the
+ *    head-wise variant of the ablation (Table 3c).
+ *  - Supported: D in {64,128}; dt in {EC_F32, EC_BF16}; multi-head attention
+ *    with as many key/value heads as query heads.
+ */
+#ifndef EC_H_
+#define EC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EC_OK = 0,
+    EC_EINVAL = 1,       /* bad shape, NULL required pointer, index out of range   */
+    EC_EUNSUPPORTED = 2, /* valid request the kernels do not cover (D, dtype, ...) */
+    EC_EWORKSPACE = 3,   /* ws NULL or smaller than ec_workspace_bytes             */
+    EC_EDEVICE = 4       /* HIP runtime reported an error at launch                */
+} ec_status;
+
+typedef enum { EC_F32 = 0, EC_BF16 = 1 } ec_dtype;
+
+typedef enum {
+    EC_FN_PREFILL_SCORE = 0,
+    EC_FN_SELECT_ANCHORS = 1,
+    EC_FN_MERGE_COMPACT = 2,
+    EC_FN_DECODE_STEP = 3
+} ec_fn;
+
+/* Budget rule of the retention test (Sec. 3.3 Output Generation; Alg. 1). */
+typedef enum {
+    EC_BUDGET_RATIO = 0, /* keep ceil(gamma * n) rows: Alg. 1's int(seq_len - n(1-r)) >= 1 test */
+    EC_BUDGET_FIXED = 1  /* keep a constant number of rows                                  */
+} ec_budget_mode;
+
+/* Truncation location of the fixed-point elimination (Sec. 3.3; Sec. 4.1). */
+typedef enum {
+    EC_TRUNC_RECENT = 0, /* `recent` rows before the newest one (25 in Sec. 4.1) */
+    EC_TRUNC_ABS = 1     /* absolute location N_tl                              */
+} ec_trunc_mode;
+
+/* Human-readable name of a status code.  Host, pure. */
+const char* ec_status_string(int status);
+
+/*
+ * Bytes of workspace the given entry point needs for these shapes.  Host, pure.
+ * For EC_FN_DECODE_STEP pass T = cap.  Returns 0 for entry points that need none
+ * and (size_t)-1 for unsupported shapes.
+ */
+size_t ec_workspace_bytes(int fn, int B, int H, int T, int D, int dt);
+
+/*
+ * Instruction-encoding attention with importance scores (Sec. 3.3, Eq. 1 and the
+ * definition of I_n that follows it).  For every (b,h):
+ *     A     = row-softmax over n <= m of scale * <q_m, k_n>      (T x T, never stored)
+ *     out_m = sum_n A_mn v_n,   lse_m = log sum_{n<=m} exp(scale <q_m,k_n>)
+ *     I_n   = sum_{m>=n} A_mn                                    (column mass)
+ * score[b,g,n] = I_n of head g when G == H, or the mean of I_n over the H heads
+ * when G == 1 (the paper's layer-wise metric).  scale = 1 gives Eq. 1 literally;
+ * models use 1/sqrt(D).
+ *   q,k,v  DEVICE [B,H,T,D] dt, read only
+ *   out    DEVICE [B,H,T,D] dt, written; may be NULL (attention output not wanted)
+ *   lse    DEVICE [B,H,T] float, written; may be NULL (kept in ws instead)
+ *   score  DEVICE [B,G,T] float, written
+ *   ws     DEVICE scratch, ec_workspace_bytes(EC_FN_PREFILL_SCORE, B,H,T,D,dt)
+ * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; fp32
+ * inputs use fp32 arithmetic throughout.  Results are deterministic.
+ */
+int ec_prefill_score(const void* q, const void* k, const void* v, void* out, float* lse,
+                     float* score, int B, int H, int G, int T, int D, int dt, float scale,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Anchor selection (Sec. 3.3: "top N_I tokens in I_n, indices in ascending
+ * order"; Sec. 4.1: the first and the most recent token are protected).
+ * For every (b,g): positions 0..protect_first-1 and T-protect_last..T-1 are
+ * always selected; of the others the n_anchor - protect_first - protect_last
+ * with the largest score are selected, equal scores going to the lower position.
+ * Scores are compared as fp32 values (-0 == +0); NaN is outside the domain.
+ *   score       DEVICE [B,G,T] float, read only
+ *   anchor_idx  DEVICE [B,G,n_anchor] int32, written, strictly ascending
+ * Requires 1 <= n_anchor <= T <= 65536, protect_first + protect_last <= n_anchor.
+ * N_I = ceil(gamma*T) is the caller's to compute (Alg. 1's del_num rounding).
+ */
+int ec_select_anchors(const float* score, int B, int G, int T, int n_anchor, int protect_first,
+                      int protect_last, int32_t* anchor_idx, void* ws, size_t ws_bytes,
+                      void* stream);
+
+/*
+ * Bucket division, cache merging and compaction (Sec. 3.3, Eq. 2 and Eq. 3;
+ * Alg. 1's Nearest / scatter_reduce / gather).  With anchors t_0 < ... < t_{n-1}
+ * bucket j holds positions floor((t_{j-1}+t_j)/2)+1 .. floor((t_j+t_{j+1})/2), the
+ * first bucket starting at 0 and the last ending at T-1 (every position goes to
+ * its nearest anchor, ties to the earlier one).  For every head, cache row j is
+ * the mean of the K (resp. V) rows of bucket j, accumulated in fp32 in ascending
+ * position and rounded once (to nearest even) to dt.
+ *   k,v              DEVICE [B,H,T,D] dt, read only
+ *   anchor_idx       DEVICE [B,G,n_anchor] int32 ascending, read only
+ *   k_cache,v_cache  DEVICE [B,H,cap,D] dt; rows 0..n_anchor-1 written, rest untouched
+ *   counts           DEVICE [B,G,n_anchor] int32 bucket sizes, written; may be NULL
+ *   assign           DEVICE [B,G,T] int32 bucket number of every position; may be NULL
+ *   pos              DEVICE [B,G,cap] int32; entries 0..n_anchor-1 = anchor positions;
+ *                    may be NULL
+ * Requires 1 <= n_anchor <= min(T, cap).  Anchors that are not strictly ascending
+ * inside [0,T) give unspecified cache contents (no out-of-bounds access).
+ */
+int ec_merge_compact(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G,
+                     int T, int D, int n_anchor, int dt, void* k_cache, void* v_cache, int cap,
+                     int32_t* counts, int32_t* assign, int32_t* pos, void* stream);
+
+/*
+ * Retention test and truncation location of the fixed-point elimination
+ * (Sec. 3.3 Output Generation; Alg. 1's del_num and fix_idx; Sec. 4.1: recent
+ * distance 25).  Host, pure integer arithmetic.
+ *   n_seen            tokens seen so far, including the one just appended
+ *   len_after_append  cache rows including the new one
+ *   gamma_num/den     retention ratio gamma as an exact fraction
+ *   budget_mode       EC_BUDGET_RATIO: evict iff len_after_append > ceil(gamma*n_seen)
+ *                     EC_BUDGET_FIXED: evict iff len_after_append > fixed_len
+ *   trunc_mode        EC_TRUNC_RECENT: idx = len_after_append - 1 - recent
+ *                     EC_TRUNC_ABS:    idx = n_tl
+ *   protect_first     rows below this index are never evicted (idx is raised to it)
+ * Returns the row to evict, or -1 for none (also when the only candidate would
+ * be the newest row), or -2 on invalid arguments.
+ */
+int ec_evict_index(int64_t n_seen, int len_after_append, int gamma_num, int gamma_den,
+                   int budget_mode, int fixed_len, int trunc_mode, int recent, int n_tl,
+                   int protect_first);
+
+/*
+ * One output-generation step of one layer over the compressed cache (Sec. 3.1
+ * Output Generation; Sec. 3.3 fixed-point elimination; Alg. 1's last branch).
+ * For every (b,h), in this order:
+ *   1. row cache_len of k_cache/v_cache <- k_new/v_new        (pos <- new_pos)
+ *   2. out = softmax_j(scale * <q, k_cache_j>) . v_cache over rows 0..cache_len
+ *      (plain softmax; merged rows carry no count weights)
+ *   3. if evict_idx >= 0, row evict_idx is removed and the rows behind it move
+ *      up by one (Alg. 1's cat of the two sides); the cache then holds
+ *      cache_len rows, else cache_len + 1.
+ *   q,k_new,v_new     DEVICE [B,H,D] dt, read only
+ *   k_cache,v_cache   DEVICE [B,H,cap,D] dt, updated in place
+ *   pos               DEVICE [B,G,cap] int32 original position of every row, updated
+ *                     like the cache; may be NULL
+ *   out               DEVICE [B,H,D] dt, written
+ *   ws                DEVICE scratch, ec_workspace_bytes(EC_FN_DECODE_STEP,B,H,cap,D,dt).
+ *                     Must be zero-filled before its first use; every completed
+ *                     call leaves it ready for the next one.  Calls that share a
+ *                     ws must not overlap.
+ * Requires 0 <= cache_len < cap and -1 <= evict_idx <= cache_len.  Dot products
+ * and the softmax are evaluated in fp32.
+ */
+int ec_decode_step(const void* q, const void* k_new, const void* v_new, void* k_cache,
+                   void* v_cache, int32_t* pos, int B, int H, int G, int D, int cap, int cache_len,
+                   int evict_idx, int32_t new_pos, float scale, int dt, void* out, void* ws,
+                   size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EC_H_ */
