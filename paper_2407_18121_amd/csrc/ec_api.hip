@@ -1,0 +1,179 @@
+// C ABI of libelastic_cache: argument validation, workspace carving and dispatch.
+// No state, no allocation; every launch goes to the caller's stream.
+#include <cstdlib>
+
+#include "ec_common.h"
+
+namespace ec {
+size_t decode_workspace_bytes(int B, int H, int D);
+int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                    int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
+                    int32_t new_pos, float scale, int dt, void* out, void* ws, int forced_splits,
+                    hipStream_t stream);
+int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G, int T,
+                   int D, int n_anchor, int dt, void* k_cache, void* v_cache, int cap, int32_t* counts,
+                   int32_t* assign, int32_t* pos, hipStream_t stream);
+int select_dispatch(const float* score, int B, int G, int T, int n_anchor, int protect_first,
+                    int protect_last, int32_t* anchor_idx, hipStream_t stream);
+int score_simt_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
+                        float* head_imp, int B, int H, int T, int D, int dt, float scale,
+                        hipStream_t stream);
+int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
+                        float* head_imp, int B, int H, int T, int D, int dt, float scale,
+                        hipStream_t stream);
+int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, hipStream_t stream);
+}  // namespace ec
+
+namespace {
+
+bool shape_supported(int D, int dt) { return (D == 64 || D == 128) && (dt == EC_F32 || dt == EC_BF16); }
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Tuning/debug switches read from the environment on every call (host only).
+int env_int(const char* name, int dflt)
+{
+    const char* s = std::getenv(name);
+    return s ? std::atoi(s) : dflt;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ec_status_string(int status)
+{
+    switch (status) {
+        case EC_OK: return "EC_OK";
+        case EC_EINVAL: return "EC_EINVAL: invalid argument";
+        case EC_EUNSUPPORTED: return "EC_EUNSUPPORTED: shape or type not covered";
+        case EC_EWORKSPACE: return "EC_EWORKSPACE: workspace missing or too small";
+        case EC_EDEVICE: return "EC_EDEVICE: HIP launch error";
+        default: return "unknown ec_status";
+    }
+}
+
+size_t ec_workspace_bytes(int fn, int B, int H, int T, int D, int dt)
+{
+    if (B < 1 || H < 1 || T < 1) return (size_t)-1;
+    switch (fn) {
+        case EC_FN_PREFILL_SCORE:
+            if (!shape_supported(D, dt)) return (size_t)-1;
+            // per-head importance [B,H,T] + row log-sum-exp [B,H,T], fp32
+            return 2 * align256((size_t)B * H * T * sizeof(float));
+        case EC_FN_SELECT_ANCHORS: return 0;
+        case EC_FN_MERGE_COMPACT: return 0;
+        case EC_FN_DECODE_STEP:
+            if (!shape_supported(D, dt)) return (size_t)-1;
+            return align256(ec::decode_workspace_bytes(B, H, D));
+        default: return (size_t)-1;
+    }
+}
+
+int ec_prefill_score(const void* q, const void* k, const void* v, void* out, float* lse, float* score,
+                     int B, int H, int G, int T, int D, int dt, float scale, void* ws, size_t ws_bytes,
+                     void* stream)
+{
+    if (!q || !k || !v || !score) return EC_EINVAL;
+    if (B < 1 || H < 1 || T < 1 || D < 1) return EC_EINVAL;
+    if (G != 1 && G != H) return EC_EINVAL;
+    if (!(scale == scale)) return EC_EINVAL;
+    if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
+    if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
+    const size_t need = ec_workspace_bytes(EC_FN_PREFILL_SCORE, B, H, T, D, dt);
+    if (!ws || ws_bytes < need) return EC_EWORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    float* ws_imp = reinterpret_cast<float*>(ws);
+    float* ws_lse = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + need / 2);
+    float* lse_buf = lse ? lse : ws_lse;
+    float* head_imp = (G == H) ? score : ws_imp;
+
+    int rc;
+    const bool use_mfma = (dt == EC_BF16) && !env_int("EC_SCORE_FORCE_SIMT", 0);
+    if (use_mfma)
+        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, B, H, T, D, dt, scale, s);
+    else
+        rc = ec::score_simt_dispatch(q, k, v, out, lse_buf, head_imp, B, H, T, D, dt, scale, s);
+    if (rc != EC_OK) return rc;
+    if (G == 1) rc = ec::head_mean_launch(head_imp, score, B, H, T, s);
+    return rc;
+}
+
+int ec_select_anchors(const float* score, int B, int G, int T, int n_anchor, int protect_first,
+                      int protect_last, int32_t* anchor_idx, void* ws, size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    if (!score || !anchor_idx) return EC_EINVAL;
+    if (B < 1 || G < 1 || T < 1 || n_anchor < 1 || n_anchor > T) return EC_EINVAL;
+    if (protect_first < 0 || protect_last < 0) return EC_EINVAL;
+    if ((long long)protect_first + protect_last > n_anchor) return EC_EINVAL;
+    if (T > 65536) return EC_EUNSUPPORTED;
+    return ec::select_dispatch(score, B, G, T, n_anchor, protect_first, protect_last, anchor_idx,
+                               reinterpret_cast<hipStream_t>(stream));
+}
+
+int ec_merge_compact(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G, int T,
+                     int D, int n_anchor, int dt, void* k_cache, void* v_cache, int cap, int32_t* counts,
+                     int32_t* assign, int32_t* pos, void* stream)
+{
+    if (!k || !v || !anchor_idx || !k_cache || !v_cache) return EC_EINVAL;
+    if (B < 1 || H < 1 || T < 1 || D < 1 || cap < 1) return EC_EINVAL;
+    if (G != 1 && G != H) return EC_EINVAL;
+    if (n_anchor < 1 || n_anchor > T || n_anchor > cap) return EC_EINVAL;
+    if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
+    if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
+    return ec::merge_dispatch(k, v, anchor_idx, B, H, G, T, D, n_anchor, dt, k_cache, v_cache, cap, counts,
+                              assign, pos, reinterpret_cast<hipStream_t>(stream));
+}
+
+int ec_evict_index(int64_t n_seen, int len_after_append, int gamma_num, int gamma_den, int budget_mode,
+                   int fixed_len, int trunc_mode, int recent, int n_tl, int protect_first)
+{
+    if (n_seen < 1 || len_after_append < 1 || protect_first < 0) return -2;
+    if (budget_mode != EC_BUDGET_RATIO && budget_mode != EC_BUDGET_FIXED) return -2;
+    if (trunc_mode != EC_TRUNC_RECENT && trunc_mode != EC_TRUNC_ABS) return -2;
+    int64_t keep;
+    if (budget_mode == EC_BUDGET_RATIO) {
+        if (gamma_den < 1 || gamma_num < 0 || gamma_num > gamma_den) return -2;
+        const int64_t prod = (int64_t)gamma_num * n_seen;
+        keep = prod / gamma_den + ((prod % gamma_den) ? 1 : 0);
+    } else {
+        if (fixed_len < 1) return -2;
+        keep = fixed_len;
+    }
+    if (len_after_append <= keep) return -1;
+    int64_t victim;
+    if (trunc_mode == EC_TRUNC_RECENT) {
+        if (recent < 0) return -2;
+        victim = (int64_t)len_after_append - 1 - recent;
+    } else {
+        if (n_tl < 0) return -2;
+        victim = n_tl;
+    }
+    if (victim < protect_first) victim = protect_first;
+    if (victim >= (int64_t)len_after_append - 1) return -1;
+    return (int)victim;
+}
+
+int ec_decode_step(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                   int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
+                   int32_t new_pos, float scale, int dt, void* out, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!q || !k_new || !v_new || !k_cache || !v_cache || !out) return EC_EINVAL;
+    if (B < 1 || H < 1 || D < 1 || cap < 1) return EC_EINVAL;
+    if (G != 1 && G != H) return EC_EINVAL;
+    if (cache_len < 0 || cache_len >= cap) return EC_EINVAL;
+    if (evict_idx < -1 || evict_idx > cache_len) return EC_EINVAL;
+    if (!(scale == scale)) return EC_EINVAL;
+    if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
+    if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
+    const size_t need = ec_workspace_bytes(EC_FN_DECODE_STEP, B, H, cap, D, dt);
+    if (!ws || ws_bytes < need) return EC_EWORKSPACE;
+    return ec::decode_dispatch(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, D, cap, cache_len, evict_idx,
+                               new_pos, scale, dt, out, ws, env_int("EC_DECODE_SPLITS", 0),
+                               reinterpret_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

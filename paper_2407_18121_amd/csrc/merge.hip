@@ -1,0 +1,139 @@
+// ec_merge_compact: bucket division (Sec. 3.3, Eq. 2), cache merging (Eq. 3) and
+// compaction (Alg. 1's gather) in one pass over K and V.
+//
+// HBM-bound: every prompt K/V row is read once, every cache row written once.
+// Buckets are contiguous position ranges, so the rows of bucket j are one
+// contiguous slab of memory.  A group of LPR = row_bytes/16 lanes owns bucket j:
+// it derives the bucket's bounds from the three neighbouring anchors, streams the
+// slab with 16-byte loads in ascending position, accumulates in fp32, divides by
+// the count once and stores the row.  Neighbouring groups own neighbouring
+// buckets, so a wave reads one contiguous stretch of the prompt.
+#include "ec_common.h"
+
+namespace ec {
+
+constexpr int kMergeThreads = 256;
+constexpr int kMergeUnroll = 4;
+
+// Inclusive bounds of bucket j for ascending anchors a[0..n).  Clamped so that a
+// malformed anchor list can never index outside [0,T).
+__device__ __forceinline__ void bucket_bounds(const int32_t* __restrict__ a, int j, int n, int T,
+                                              int& lo, int& hi)
+{
+    const int t = a[j];
+    lo = (j == 0) ? 0 : ((a[j - 1] + t) >> 1) + 1;
+    hi = (j == n - 1) ? T - 1 : ((t + a[j + 1]) >> 1);
+    lo = max(lo, 0);
+    hi = min(hi, T - 1);
+}
+
+template <int DT, int D>
+__global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
+    const uint4* __restrict__ k, const uint4* __restrict__ v, const int32_t* __restrict__ anchor_idx,
+    uint4* __restrict__ k_cache, uint4* __restrict__ v_cache, int H, int G, int T, int n_anchor, int cap)
+{
+    constexpr int LPR = D * Elem<DT>::kBytes / 16;
+    constexpr int EPL = Elem<DT>::kPerChunk;
+    constexpr int GROUPS = kMergeThreads / LPR;
+    const int bh = blockIdx.y;
+    const int b = bh / H, h = bh % H;
+    const int sub = threadIdx.x % LPR;
+    const int j = blockIdx.x * GROUPS + threadIdx.x / LPR;
+    if (j >= n_anchor) return;
+
+    const int32_t* a = anchor_idx + ((size_t)b * G + (G == 1 ? 0 : h)) * n_anchor;
+    int lo, hi;
+    bucket_bounds(a, j, n_anchor, T, lo, hi);
+
+    const uint4* src = (blockIdx.z == 0 ? k : v) + (size_t)bh * T * LPR + sub;
+    uint4* dst = (blockIdx.z == 0 ? k_cache : v_cache) + ((size_t)bh * cap + j) * LPR + sub;
+
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+
+    int t = lo;
+    for (; t + kMergeUnroll - 1 <= hi; t += kMergeUnroll) {
+        uint4 c[kMergeUnroll];
+#pragma unroll
+        for (int u = 0; u < kMergeUnroll; ++u) c[u] = src[(size_t)(t + u) * LPR];
+#pragma unroll
+        for (int u = 0; u < kMergeUnroll; ++u) {
+            float x[EPL];
+            unpack<DT>(c[u], x);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] += x[e];
+        }
+    }
+    for (; t <= hi; ++t) {
+        float x[EPL];
+        unpack<DT>(src[(size_t)t * LPR], x);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] += x[e];
+    }
+    const int count = hi - lo + 1;
+    if (count > 1) {
+        const float cf = (float)count;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] = acc[e] / cf;
+    }
+    *dst = pack<DT>(acc);
+}
+
+// Bookkeeping per score group: bucket sizes, bucket number of every position,
+// original position of every cache row.
+__global__ __launch_bounds__(256) void bucket_meta_kernel(const int32_t* __restrict__ anchor_idx,
+                                                          int T, int n_anchor, int cap,
+                                                          int32_t* __restrict__ counts,
+                                                          int32_t* __restrict__ assign,
+                                                          int32_t* __restrict__ pos)
+{
+    const int bg = blockIdx.y;
+    const int32_t* a = anchor_idx + (size_t)bg * n_anchor;
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < n_anchor; j += gridDim.x * blockDim.x) {
+        int lo, hi;
+        bucket_bounds(a, j, n_anchor, T, lo, hi);
+        if (counts) counts[(size_t)bg * n_anchor + j] = hi - lo + 1;
+        if (pos) pos[(size_t)bg * cap + j] = a[j];
+        if (assign)
+            for (int t = lo; t <= hi; ++t) assign[(size_t)bg * T + t] = j;
+    }
+}
+
+template <int DT, int D>
+static int launch_merge(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G,
+                        int T, int n_anchor, void* k_cache, void* v_cache, int cap, hipStream_t stream)
+{
+    constexpr int LPR = D * Elem<DT>::kBytes / 16;
+    constexpr int GROUPS = kMergeThreads / LPR;
+    dim3 grid((n_anchor + GROUPS - 1) / GROUPS, B * H, 2);
+    hipLaunchKernelGGL((merge_compact_kernel<DT, D>), grid, dim3(kMergeThreads), 0, stream,
+                       (const uint4*)k, (const uint4*)v, anchor_idx, (uint4*)k_cache, (uint4*)v_cache,
+                       H, G, T, n_anchor, cap);
+    return status_from_hip(hipGetLastError());
+}
+
+int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G, int T,
+                   int D, int n_anchor, int dt, void* k_cache, void* v_cache, int cap, int32_t* counts,
+                   int32_t* assign, int32_t* pos, hipStream_t stream)
+{
+    int rc = EC_EUNSUPPORTED;
+#define EC_MERGE_CASE(DT_, D_)                                                                      \
+    if (dt == DT_ && D == D_)                                                                       \
+        rc = launch_merge<DT_, D_>(k, v, anchor_idx, B, H, G, T, n_anchor, k_cache, v_cache, cap, stream);
+    EC_MERGE_CASE(EC_BF16, 128)
+    EC_MERGE_CASE(EC_BF16, 64)
+    EC_MERGE_CASE(EC_F32, 128)
+    EC_MERGE_CASE(EC_F32, 64)
+#undef EC_MERGE_CASE
+    if (rc != EC_OK) return rc;
+    if (counts || assign || pos) {
+        dim3 grid((n_anchor + 255) / 256, B * G);
+        hipLaunchKernelGGL(bucket_meta_kernel, grid, dim3(256), 0, stream, anchor_idx, T, n_anchor, cap,
+                           counts, assign, pos);
+        rc = status_from_hip(hipGetLastError());
+    }
+    return rc;
+}
+
+}  // namespace ec

@@ -1,0 +1,142 @@
+// ec_select_anchors: per (batch, score group) choice of the N_I highest-scoring
+// positions (Sec. 3.3), protected first/last positions always kept (Sec. 4.1),
+// equal scores resolved toward the lower position, output ascending.
+//
+// One workgroup of 1024 threads per problem.  Scores are mapped to 32-bit keys
+// whose unsigned order equals the fp32 order (-0 folded onto +0).  An MSB-first
+// radix select (four 8-bit digits, LDS histograms) finds the key of the last
+// selected element and how many elements equal to it are needed; one ordered
+// sweep over the positions then emits the selected indices in ascending order,
+// taking equal keys lowest-position-first.  Pure integer work: the result is
+// bit-exact by construction.
+#include "ec_common.h"
+
+namespace ec {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / kWave;
+constexpr int kSelLdsKeys = 8192;  // keys are cached in LDS up to this T
+
+__device__ __forceinline__ uint32_t score_key(float s)
+{
+    uint32_t u = __float_as_uint(s);
+    if (u == 0x80000000u) u = 0u;  // -0 compares equal to +0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Exclusive prefix of a per-thread flag over the workgroup; returns the total in `total`.
+__device__ __forceinline__ int block_excl_scan_flag(bool flag, int* wave_tot /*[kSelWaves]*/, int& total)
+{
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const unsigned long long ball = __ballot(flag);
+    const int in_wave = __popcll(ball & ((1ull << lane) - 1ull));
+    __syncthreads();  // previous users of wave_tot are done
+    if (lane == 0) wave_tot[wave] = __popcll(ball);
+    __syncthreads();
+    int before = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) {
+        const int c = wave_tot[w];
+        before += (w < wave) ? c : 0;
+        tot += c;
+    }
+    total = tot;
+    return before + in_wave;
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_anchors_kernel(
+    const float* __restrict__ score, int T, int n_anchor, int protect_first, int protect_last,
+    int32_t* __restrict__ anchor_idx, int keys_in_lds)
+{
+    extern __shared__ uint32_t lds_keys[];
+    __shared__ int hist[256];
+    __shared__ int suffix[256];
+    __shared__ int wave_tot[kSelWaves];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_need;
+
+    const int tid = threadIdx.x;
+    const float* s = score + (size_t)blockIdx.x * T;
+    int32_t* dst = anchor_idx + (size_t)blockIdx.x * n_anchor;
+    const int free_lo = protect_first, free_hi = T - protect_last;  // unprotected: [free_lo, free_hi)
+    const int n_free = n_anchor - protect_first - protect_last;
+
+    if (keys_in_lds)
+        for (int t = tid; t < T; t += kSelThreads) lds_keys[t] = score_key(s[t]);
+    if (tid == 0) {
+        sh_prefix = 0u;
+        sh_need = n_free;
+    }
+    __syncthreads();
+
+    // ---- radix select of the n_free-th largest unprotected key ----
+    if (n_free > 0) {
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            const uint32_t hi_mask = (pass == 0) ? 0u : (0xffffffffu << (shift + 8));
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            const uint32_t prefix = sh_prefix;
+            const int need = sh_need;
+            for (int t = free_lo + tid; t < free_hi; t += kSelThreads) {
+                const uint32_t key = keys_in_lds ? lds_keys[t] : score_key(s[t]);
+                if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xffu], 1);
+            }
+            __syncthreads();
+            // suffix[d] = number of candidates with digit > d  (inclusive scan from the top)
+            if (tid < 256) suffix[tid] = hist[tid];
+            __syncthreads();
+            for (int off = 1; off < 256; off <<= 1) {
+                int add = 0;
+                if (tid < 256 && tid + off < 256) add = suffix[tid + off];
+                __syncthreads();
+                if (tid < 256) suffix[tid] += add;
+                __syncthreads();
+            }
+            if (tid < 256) {
+                const int above = suffix[tid] - hist[tid];  // candidates with a larger digit
+                if (above < need && need <= suffix[tid]) {  // exactly one digit satisfies this
+                    sh_prefix = prefix | ((uint32_t)tid << shift);
+                    sh_need = need - above;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    const uint32_t kth = sh_prefix;  // key of the last selected unprotected element
+    const int need_eq = sh_need;     // how many elements equal to kth are selected (lowest positions)
+
+    // ---- ordered emission ----
+    int base_eq = 0, base_out = 0;
+    for (int t0 = 0; t0 < T; t0 += kSelThreads) {
+        const int t = t0 + tid;
+        bool prot = false, gt = false, eq = false;
+        if (t < T) {
+            prot = (t < free_lo) || (t >= free_hi);
+            if (!prot && n_free > 0) {
+                const uint32_t key = keys_in_lds ? lds_keys[t] : score_key(s[t]);
+                gt = key > kth;
+                eq = key == kth;
+            }
+        }
+        int tot_eq, tot_out;
+        const int eq_rank = base_eq + block_excl_scan_flag(eq, wave_tot, tot_eq);
+        const bool sel = prot || gt || (eq && eq_rank < need_eq);
+        const int o = base_out + block_excl_scan_flag(sel, wave_tot, tot_out);
+        if (sel && o < n_anchor) dst[o] = t;
+        base_eq += tot_eq;
+        base_out += tot_out;
+    }
+}
+
+int select_dispatch(const float* score, int B, int G, int T, int n_anchor, int protect_first,
+                    int protect_last, int32_t* anchor_idx, hipStream_t stream)
+{
+    const int keys_in_lds = T <= kSelLdsKeys;
+    const size_t dyn = keys_in_lds ? (size_t)T * sizeof(uint32_t) : 0;
+    hipLaunchKernelGGL(select_anchors_kernel, dim3(B * G), dim3(kSelThreads), dyn, stream, score, T,
+                       n_anchor, protect_first, protect_last, anchor_idx, keys_in_lds);
+    return status_from_hip(hipGetLastError());
+}
+
+}  // namespace ec

@@ -1,0 +1,66 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol, and its
+host-only entry points (status strings, workspace sizes, retention test) behave.  No kernels run."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+from paper_2407_18121_amd import binding as ec
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ec.h")).read()
+    declared = set(re.findall(r"\b(ec_[a-z_]+)\s*\(", header))
+    assert declared == set(ec.SYMBOLS), declared ^ set(ec.SYMBOLS)
+    lib = ctypes.CDLL(ec.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings_and_workspace_sizes():
+    assert ec.status_string(ec.EC_OK) == "EC_OK"
+    for code in (1, 2, 3, 4):
+        assert ec.status_string(code).startswith("EC_E")
+    assert ec.ec_workspace_bytes(ec.EC_FN_SELECT_ANCHORS, 1, 1, 16, 64, ec.EC_F32) == 0
+    n = ec.ec_workspace_bytes(ec.EC_FN_PREFILL_SCORE, 2, 4, 100, 64, ec.EC_F32)
+    assert n >= 2 * 2 * 4 * 100 * 4 and n % 256 == 0
+    assert ec.ec_workspace_bytes(ec.EC_FN_DECODE_STEP, 2, 4, 100, 128, ec.EC_BF16) > 0
+    with pytest.raises(ec.EcError):
+        ec.ec_workspace_bytes(ec.EC_FN_DECODE_STEP, 2, 4, 100, 96, ec.EC_BF16)
+
+
+def test_invalid_arguments_are_rejected_before_any_launch():
+    lib = ec.load()
+    # NULL pointers / bad shapes: the host returns before touching the device
+    assert lib.ec_select_anchors(None, 1, 1, 8, 4, 1, 1, None, None, 0, None) == ec.EC_EINVAL
+    assert lib.ec_merge_compact(None, None, None, 1, 1, 1, 8, 64, 4, 0, None, None, 4, None, None, None, None) == ec.EC_EINVAL
+    assert lib.ec_decode_step(None, None, None, None, None, None, 1, 1, 1, 64, 8, 0, -1, 0, 1.0, 0, None, None, 0, None) == ec.EC_EINVAL
+    assert lib.ec_prefill_score(None, None, None, None, None, None, 1, 1, 1, 8, 64, 0, 1.0, None, 0, None) == ec.EC_EINVAL
+    one = ctypes.c_void_p(256)  # never dereferenced: validation fails first
+    assert lib.ec_select_anchors(one, 1, 1, 8, 9, 1, 1, one, None, 0, None) == ec.EC_EINVAL       # n_anchor > T
+    assert lib.ec_select_anchors(one, 1, 1, 8, 2, 2, 1, one, None, 0, None) == ec.EC_EINVAL       # protected > n_anchor
+    assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 64, 8, 8, -1, 0, 1.0, 0, one, one, 1 << 20, None) == ec.EC_EINVAL  # full
+    assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 64, 8, 3, 4, 0, 1.0, 0, one, one, 1 << 20, None) == ec.EC_EINVAL   # evict > len
+    assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 96, 8, 3, 1, 0, 1.0, 0, one, one, 1 << 20, None) == ec.EC_EUNSUPPORTED
+    assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 64, 8, 3, 1, 0, 1.0, 0, one, one, 16, None) == ec.EC_EWORKSPACE
+    assert lib.ec_merge_compact(one, one, one, 1, 4, 2, 8, 64, 4, 0, one, one, 4, None, None, None, None) == ec.EC_EINVAL  # G not in {1,H}
+
+
+def test_evict_index_matches_oracle_everywhere():
+    for gamma in ((1, 2), (1, 4), (1, 10), (3, 7), (1, 1)):
+        for budget_mode, trunc_mode in ((0, 0), (1, 0), (0, 1), (1, 1)):
+            for n_seen in (1, 2, 5, 26, 27, 100, 1025, 9000):
+                for length in (1, 2, 3, 26, 27, 28, 60, 513, 900):
+                    for pf in (0, 1, 4):
+                        kw = dict(budget_mode=budget_mode, fixed_len=50, trunc_mode=trunc_mode, recent=25,
+                                  n_tl=40, protect_first=pf)
+                        assert (ec.ec_evict_index(n_seen, length, *gamma, **kw)
+                                == oracle.evict_index(n_seen, length, *gamma, **kw)), (gamma, kw, n_seen, length)
+    with pytest.raises(ec.EcError):
+        ec.ec_evict_index(0, 5, 1, 2)
+    with pytest.raises(ec.EcError):
+        ec.ec_evict_index(5, 5, 3, 2)

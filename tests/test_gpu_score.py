@@ -1,0 +1,59 @@
+"""GPU parity: ec_prefill_score vs the CPU oracle (Sec. 3.3, Eq. 1 and the importance I_n)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2407_18121_amd import binding as ec
+from paper_2407_18121_amd import synthetic as syn
+from util import assert_close, to_dev, to_host, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gpu_score(q, k, v, dtype, scale, G, want_out=True, want_lse=True):
+    B, H, T, D = q.shape
+    dq, dk, dv = to_dev(q, dtype), to_dev(k, dtype), to_dev(v, dtype)
+    out = torch.full((B, H, T, D), float("nan"), dtype=torch_dtype(dtype), device="cuda") if want_out else None
+    lse = torch.full((B, H, T), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
+    score = torch.full((B, G, T), float("nan"), dtype=torch.float32, device="cuda")
+    ws = ec.new_workspace(ec.EC_FN_PREFILL_SCORE, B, H, T, D, ec.dtype_code(dq))
+    ec.ec_prefill_score(dq, dk, dv, out, lse, score, scale, ws)
+    torch.cuda.synchronize()
+    return (None if out is None else to_host(out), None if lse is None else to_host(lse), to_host(score))
+
+
+@pytest.mark.parametrize("dtype,D", [("f32", 64), ("bf16", 128), ("bf16", 64), ("f32", 128)])
+@pytest.mark.parametrize("B,H,T,Gmode", [(1, 2, 1, "layer"), (2, 3, 37, "head"), (1, 4, 256, "layer"),
+                                         (2, 2, 321, "layer"), (1, 2, 700, "head")])
+def test_prefill_score_parity(dtype, D, B, H, T, Gmode):
+    cfg = syn.custom("t", H=H, D=D, B=B, T=T, dtype=dtype, cid=1000 + T)
+    q, k, v = syn.prompt_qkv(cfg)
+    G = 1 if Gmode == "layer" else H
+    ref = oracle.prefill_score(q, k, v, cfg.scale, G)
+    out, lse, score = run_gpu_score(q, k, v, dtype, cfg.scale, G)
+    assert_close(out, ref["out"], dtype, "out")
+    assert_close(lse, ref["lse"], dtype, "lse")
+    assert_close(score, ref["score"], dtype, "score")
+    np.testing.assert_allclose(score.sum(-1), T, rtol=1e-5)          # rows of A sum to one
+
+
+def test_prefill_score_optional_outputs_and_literal_eq1_scale():
+    cfg = syn.custom("t", H=2, D=64, B=1, T=150, dtype="f32", cid=1234)
+    q, k, v = syn.prompt_qkv(cfg)
+    q = (q * 0.2).astype(np.float32)
+    ref = oracle.prefill_score(q, k, v, 1.0, 1)
+    out, lse, score = run_gpu_score(q, k, v, "f32", 1.0, 1, want_out=False, want_lse=False)
+    assert out is None and lse is None
+    assert_close(score, ref["score"], "f32", "score")
+
+
+def test_tiny_config_full_layer():
+    cfg = syn.CONFIGS["C1"]
+    q, k, v = syn.prompt_qkv(cfg)
+    for G in (1, cfg.H):
+        ref = oracle.prefill_score(q, k, v, cfg.scale, G)
+        out, lse, score = run_gpu_score(q, k, v, cfg.dtype, cfg.scale, G)
+        assert_close(out, ref["out"], cfg.dtype, "out")
+        assert_close(lse, ref["lse"], cfg.dtype, "lse")
+        assert_close(score, ref["score"], cfg.dtype, "score")
