@@ -1,0 +1,322 @@
+#!/usr/bin/env python3
+"""Benchmark of the Elastic Cache hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic prompts:
+for every layer ec_prefill_score -> ec_select_anchors -> ec_merge_compact, then
+`decode_steps` generated tokens, each walking every layer with ec_evict_index
+(host) -> ec_decode_step on that layer's own compressed cache.  All inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--score-mode layer|head]
+                    [--no-graph] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
+FP32_VALU_PEAK_TFLOPS = 157.3
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--score-mode", default="layer", choices=["layer", "head"])
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--distinct-layers", type=int, default=0,
+                    help="distinct prompt tensors to generate (0 = one per layer; fewer are cycled)")
+    return ap.parse_args()
+
+
+class Workload:
+    """Device buffers + the precomputed call list of one hot-path step."""
+
+    def __init__(self, cfg, score_mode, distinct_layers):
+        import torch
+        from paper_2407_18121_amd import binding as ec
+        from paper_2407_18121_amd import synthetic_torch as synt
+        self.cfg, self.ec, self.torch = cfg, ec, torch
+        self.lib = ec.load()
+        dt = synt.torch_dtype(cfg)
+        self.dt_code = ec.EC_F32 if cfg.dtype == "f32" else ec.EC_BF16
+        B, H, T, D, L = cfg.B, cfg.H, cfg.T, cfg.D, cfg.layers
+        self.G = 1 if score_mode == "layer" else H
+        n_distinct = L if distinct_layers <= 0 else min(L, distinct_layers)
+        self.prompts = [synt.prompt_qkv_device(cfg, l) for l in range(n_distinct)]
+        self.dec = [synt.decode_stream_device(cfg, l) for l in range(L)]
+        cap, nA, G = cfg.cap, cfg.n_anchor, self.G
+        self.k_cache = [torch.zeros((B, H, cap, D), dtype=dt, device="cuda") for _ in range(L)]
+        self.v_cache = [torch.zeros((B, H, cap, D), dtype=dt, device="cuda") for _ in range(L)]
+        self.pos = [torch.zeros((B, G, cap), dtype=torch.int32, device="cuda") for _ in range(L)]
+        self.score = [torch.empty((B, G, T), dtype=torch.float32, device="cuda") for _ in range(L)]
+        self.anchor = [torch.empty((B, G, nA), dtype=torch.int32, device="cuda") for _ in range(L)]
+        self.counts = [torch.empty((B, G, nA), dtype=torch.int32, device="cuda") for _ in range(L)]
+        self.attn_out = torch.empty((B, H, T, D), dtype=dt, device="cuda")  # consumed by the (absent) model
+        self.dec_out = torch.empty((B, H, D), dtype=dt, device="cuda")
+        self.ws_prefill = ec.new_workspace(ec.EC_FN_PREFILL_SCORE, B, H, T, D, self.dt_code)
+        self.ws_decode = ec.new_workspace(ec.EC_FN_DECODE_STEP, B, H, cap, D, self.dt_code)
+        self._build_calls()
+
+    def _build_calls(self):
+        cfg, lib, G = self.cfg, self.lib, self.G
+        B, H, T, D, L = cfg.B, cfg.H, cfg.T, cfg.D, cfg.layers
+        cap, nA, dtc, scale = cfg.cap, cfg.n_anchor, self.dt_code, cfg.scale
+        ws_p, ws_pb = self.ws_prefill.data_ptr(), self.ws_prefill.numel()
+        ws_d, ws_db = self.ws_decode.data_ptr(), self.ws_decode.numel()
+        self.score_calls, self.select_calls, self.merge_calls = [], [], []
+        for l in range(L):
+            q, k, v = self.prompts[l % len(self.prompts)]
+            self.score_calls.append((q.data_ptr(), k.data_ptr(), v.data_ptr(), self.attn_out.data_ptr(), None,
+                                     self.score[l].data_ptr(), B, H, G, T, D, dtc, scale, ws_p, ws_pb))
+            self.select_calls.append((self.score[l].data_ptr(), B, G, T, nA, 1, 1, self.anchor[l].data_ptr(), None, 0))
+            self.merge_calls.append((k.data_ptr(), v.data_ptr(), self.anchor[l].data_ptr(), B, H, G, T, D, nA, dtc,
+                                     self.k_cache[l].data_ptr(), self.v_cache[l].data_ptr(), cap,
+                                     self.counts[l].data_ptr(), None, self.pos[l].data_ptr()))
+        # decode schedule: the retention test is pure host integer arithmetic (Alg. 1)
+        self.decode_calls = []
+        self.decode_bytes = 0
+        p, qd = cfg.gamma
+        N = nA
+        esz = cfg.esize
+        row = D * esz
+        for step in range(cfg.decode_steps):
+            n_seen = T + step + 1
+            idx = self.ec.ec_evict_index(n_seen, N + 1, p, qd)
+            for l in range(L):
+                dq, dk, dv = self.dec[l]
+                self.decode_calls.append((dq[step].data_ptr(), dk[step].data_ptr(), dv[step].data_ptr(),
+                                          self.k_cache[l].data_ptr(), self.v_cache[l].data_ptr(), self.pos[l].data_ptr(),
+                                          B, H, G, D, cap, N, idx, n_seen - 1, scale, dtc, self.dec_out.data_ptr(),
+                                          ws_d, ws_db))
+            # algorithmic bytes of one launch: K and V rows read once (incl. the new row)
+            self.decode_bytes += L * 2 * B * H * (N + 1) * row
+            N += 0 if idx >= 0 else 1
+        self.final_len = N
+        self.score_flops_per_layer = 3.0 * D * T * (T + 1) * B * H
+        self.merge_bytes_per_layer = 2.0 * B * H * D * esz * (T + nA)
+
+    # --- launch helpers (stream = torch's current stream) ---
+    def _stream(self):
+        return self.torch.cuda.current_stream().cuda_stream
+
+    def run_score(self, s):
+        f = self.lib.ec_prefill_score
+        for a in self.score_calls:
+            rc = f(*a, s)
+            assert rc == 0, rc
+
+    def run_select(self, s):
+        f = self.lib.ec_select_anchors
+        for a in self.select_calls:
+            rc = f(*a, s)
+            assert rc == 0, rc
+
+    def run_merge(self, s):
+        f = self.lib.ec_merge_compact
+        for a in self.merge_calls:
+            rc = f(*a, s)
+            assert rc == 0, rc
+
+    def run_prefill(self, s):
+        fs, fa, fm = self.lib.ec_prefill_score, self.lib.ec_select_anchors, self.lib.ec_merge_compact
+        for a, b, c in zip(self.score_calls, self.select_calls, self.merge_calls):
+            rc = fs(*a, s) | fa(*b, s) | fm(*c, s)
+            assert rc == 0, rc
+
+    def run_decode(self, s):
+        f = self.lib.ec_decode_step
+        for a in self.decode_calls:
+            rc = f(*a, s)
+            assert rc == 0, rc
+
+
+def capture(torch, fn):
+    """Record fn(stream) into a HIP graph; returns a replay callable, or None if capture is not possible."""
+    try:
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                fn(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        return g.replay
+    except Exception as e:  # pragma: no cover
+        print(f"[bench] graph capture unavailable ({type(e).__name__}: {e}); launching eagerly", file=sys.stderr)
+        return None
+
+
+def timed(torch, fn, reps):
+    """Average milliseconds of fn() over reps, measured with HIP events on the current stream."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def cpu_baseline(cfg, wl, G):
+    """Time the fp64 oracle on a bounded sample of the same workload and scale to whole-job tokens/s."""
+    import numpy as np
+    import oracle
+    torch = wl.torch
+    B, H, T, D, L = cfg.B, cfg.H, cfg.T, cfg.D, cfg.layers
+    # prefill sample: layer 0, as many batch elements as keep the fp64 brute force near 10-20 s
+    flops_per_b = 2.0 * 2.0 * D * T * (T + 1) / 2 * H
+    nb = max(1, min(B, int(6e10 // flops_per_b)))
+    heads = H
+    if flops_per_b > 1.2e11:   # even one batch element is too long: time a subset of heads (G=H semantics)
+        heads = max(1, int(H * 1.2e11 // flops_per_b))
+    q, k, v = (x[:nb, :heads].float().cpu().numpy() for x in wl.prompts[0])
+    t0 = time.perf_counter()
+    r = oracle.prefill_score(q, k, v, cfg.scale, 1 if heads == H and G == 1 else heads, want_out=True)
+    t_score = time.perf_counter() - t0
+    sc32 = r["score"].astype(np.float32)
+    t0 = time.perf_counter()
+    a = oracle.select_anchors(sc32, cfg.n_anchor, 1, 1)
+    assign, _ = oracle.assign_nearest(a, T)
+    kc = oracle.merge_compact(k, assign, cfg.n_anchor, cfg.cap)
+    vc = oracle.merge_compact(v, assign, cfg.n_anchor, cfg.cap)
+    t_rest = time.perf_counter() - t0
+    frac = (nb * heads) / (B * H)
+    t_prefill_layer = (t_score + t_rest) / frac
+    # decode sample: a few steps of layer 0 at the first, middle and last cache length
+    lens = sorted({cfg.n_anchor, (cfg.n_anchor + wl.final_len) // 2, wl.final_len - 1})
+    dq, dk, dv = (x[:3, :nb, :heads].float().cpu().numpy() for x in wl.dec[0])
+    t_dec = []
+    for i, n in enumerate(lens):
+        n = min(n, cfg.cap - 1)
+        t0 = time.perf_counter()
+        oracle.decode_step(dq[i % 3], dk[i % 3], dv[i % 3], kc, vc, None, n, max(1, n - 25), 0, cfg.scale)
+        t_dec.append(time.perf_counter() - t0)
+    t_decode_layer_step = float(np.mean(t_dec)) / frac
+    total = L * t_prefill_layer + L * cfg.decode_steps * t_decode_layer_step
+    return {
+        "value": B * cfg.decode_steps / total, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": (f"layer 0, {nb}/{B} batch elements x {heads}/{H} heads: score+select+merge {t_score + t_rest:.2f} s, "
+                   f"{len(lens)} decode steps at cache lengths {lens} {sum(t_dec):.3f} s; scaled linearly to "
+                   f"{L} layers x {cfg.decode_steps} steps x full batch"),
+        "prefill_s_per_layer": t_prefill_layer, "decode_s_per_layer_step": t_decode_layer_step,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the hot path has no cross-GPU exchange); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2407_18121_amd import synthetic as syn
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    cfg = syn.CONFIGS[args.config]
+    wl = Workload(cfg, args.score_mode, args.distinct_layers)
+    L, B = cfg.layers, cfg.B
+    torch.cuda.synchronize()
+
+    eager_prefill = lambda: wl.run_prefill(wl._stream())
+    eager_decode = lambda: wl.run_decode(wl._stream())
+    # eager pass first: also validates every argument before anything is captured
+    eager_prefill()
+    eager_decode()
+    torch.cuda.synchronize()
+    replay_prefill = replay_decode = None
+    if not args.no_graph:
+        replay_prefill = capture(torch, wl.run_prefill)
+        replay_decode = capture(torch, wl.run_decode) if replay_prefill else None
+    use_graph = replay_prefill is not None and replay_decode is not None
+    do_prefill = replay_prefill if use_graph else eager_prefill
+    do_decode = replay_decode if use_graph else eager_decode
+
+    for _ in range(args.warmup):
+        do_prefill()
+        do_decode()
+    torch.cuda.synchronize()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_wall0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        do_prefill()
+        ev[i][1].record()
+        do_decode()
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall0) * 1e3 / args.steps
+    prefill_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    decode_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    ms_per_step = max(wall_ms, prefill_ms + decode_ms)
+
+    # ---- per-call breakdown (outside the timed region above, same buffers) ----
+    reps = 3
+    score_ms = timed(torch, lambda: wl.run_score(wl._stream()), reps) / L
+    select_ms = timed(torch, lambda: wl.run_select(wl._stream()), reps) / L
+    merge_ms = timed(torch, lambda: wl.run_merge(wl._stream()), reps) / L
+    do_prefill()  # restore the compressed caches for whoever looks at them next
+    torch.cuda.synchronize()
+
+    n_dec = len(wl.decode_calls)
+    dec_launch_us = decode_ms * 1e3 / n_dec
+    dec_gbps = wl.decode_bytes / (decode_ms * 1e-3) / 1e9
+    score_tflops = wl.score_flops_per_layer / (score_ms * 1e-3) / 1e12
+    merge_gbps = wl.merge_bytes_per_layer / (merge_ms * 1e-3) / 1e9
+    score_peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
+
+    res = {
+        "metric": "decode-attn GB/s + tokens/s over merged KV; prefill score+merge us/layer",
+        "value": B * cfg.decode_steps / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {L} layers, {cfg.H} heads, head_dim {cfg.D}, batch {B}, prompt {cfg.T}, "
+                               f"budget {cfg.gamma[0]}/{cfg.gamma[1]}, {cfg.decode_steps} decode steps, {cfg.dtype}",
+                   "score_mode": args.score_mode, "launch": "hipgraph" if use_graph else "eager",
+                   "cache_len": [cfg.n_anchor, wl.final_len]},
+        "detail": {
+            "decode_attn_GBps": dec_gbps, "decode_tokens_per_s": B * cfg.decode_steps / (decode_ms * 1e-3),
+            "decode_us_per_launch": dec_launch_us, "decode_launches": n_dec,
+            "prefill_score_merge_us_per_layer": prefill_ms * 1e3 / L,
+            "score_us_per_layer": score_ms * 1e3, "select_us_per_layer": select_ms * 1e3,
+            "merge_us_per_layer": merge_ms * 1e3,
+            "score_TFLOPs": score_tflops, "score_frac_of_peak": score_tflops / score_peak,
+            "merge_GBps": merge_gbps, "merge_frac_of_hbm_peak": merge_gbps / HBM_PEAK_GBPS,
+            "wall_ms_per_step": wall_ms, "event_ms_per_step": prefill_ms + decode_ms,
+        },
+        "roofline": {
+            "kernel": "decode_step_kernel", "bound": "hbm", "achieved": dec_gbps, "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": dec_gbps / HBM_PEAK_GBPS, "traffic": None,
+            "bytes_per_launch": wl.decode_bytes / n_dec, "us_per_launch": dec_launch_us,
+        },
+        "roofline_score": {
+            "kernel": "prefill score (attention + column mass)", "bound": "mfma" if cfg.dtype == "bf16" else "alu",
+            "achieved": score_tflops, "peak": score_peak, "unit": "TFLOP/s", "frac": score_tflops / score_peak,
+            "traffic": None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg, wl, wl.G)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -167,10 +167,8 @@ int ec_evict_index(int64_t n_seen, int len_after_append, int gamma_num, int gamm
  *   pos               DEVICE [B,G,cap] int32 original position of every row, updated
  *                     like the cache; may be NULL
  *   out               DEVICE [B,H,D] dt, written
- *   ws                DEVICE scratch, ec_workspace_bytes(EC_FN_DECODE_STEP,B,H,cap,D,dt).
- *                     Must be zero-filled before its first use; every completed
- *                     call leaves it ready for the next one.  Calls that share a
- *                     ws must not overlap.
+ *   ws                reserved: ec_workspace_bytes(EC_FN_DECODE_STEP, ...) is 0 and ws may be
+ *                     NULL (one workgroup owns a whole (batch, head); nothing is staged)
  * Requires 0 <= cache_len < cap and -1 <= evict_idx <= cache_len.  Dot products
  * and the softmax are evaluated in fp32.
  */

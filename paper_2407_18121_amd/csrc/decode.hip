@@ -3,51 +3,41 @@
 // the same launch (Sec. 3.1 Output Generation; Sec. 3.3; Alg. 1's last branch).
 //
 // HBM-bound: every K and V row of the cache is read exactly once with 16-byte
-// loads.  The rows of one (batch, head) are cut into `n_splits` contiguous
-// ranges, one workgroup each (flash-decoding style), so that small batches still
-// fill 256 CUs.  A group of LPR = row_bytes/16 lanes owns one row per load; each
-// group keeps its own running (max, sum, weighted V) and never talks to other
-// groups inside the streaming loop.  Workgroup partials go to the workspace; the
-// last workgroup of a (batch, head) to arrive -- decided by an atomic ticket --
-// merges them, writes `out`, and only then shifts the tail rows over the evicted
-// row and stores the new row, so no row is overwritten before every reader of
-// that (batch, head) is done.
+// loads.  One workgroup of up to 16 waves owns a whole (batch, head), so nothing
+// is exchanged between workgroups (a split over workgroups was measured: the
+// device-scope release/acquire it needs costs far more than the extra
+// parallelism returns on this multi-die part).  A group of LPR = row_bytes/16
+// lanes owns one row per load, so a wave load covers 1 KB of contiguous cache;
+// each group keeps its own running (max, sum, weighted V) and never talks to
+// other groups inside the streaming loop.  Loads of the next tile are issued
+// before the current tile is consumed.  Tiles are aligned to the END of the
+// cache, so when the loop finishes the registers still hold the newest rows:
+// after the workgroup barrier that ends all reads, the rows behind the evicted
+// one are stored one slot up straight from those registers, and so is the new
+// row -- the elimination costs no extra read.
 #include "ec_common.h"
 
 namespace ec {
 
-constexpr int kDecodeThreads = 256;
-constexpr int kDecodeWaves = kDecodeThreads / kWave;
-constexpr int kDecodeUnroll = 4;
-constexpr int kDecodeMaxSplits = 64;
-
-template <int DT, int D> struct DecodeShape {
+template <int DT, int D, int WAVES, int UNROLL> struct DecodeShape {
+    static constexpr int kThreads = WAVES * kWave;
     static constexpr int kRowBytes = D * Elem<DT>::kBytes;
-    static constexpr int kLPR = kRowBytes / 16;           // lanes per row
-    static constexpr int kRPW = kWave / kLPR;             // rows per wave load
-    static constexpr int kEPL = Elem<DT>::kPerChunk;      // elements per lane
-    static constexpr int kGroups = kDecodeWaves * kRPW;   // row groups per workgroup
-    static constexpr int kTile = kDecodeWaves * kDecodeUnroll * kRPW;  // rows per WG iteration
+    static constexpr int kLPR = kRowBytes / 16;                 // lanes per row
+    static constexpr int kRPW = kWave / kLPR;                   // rows per wave load
+    static constexpr int kEPL = Elem<DT>::kPerChunk;            // elements per lane
+    static constexpr int kTile = WAVES * UNROLL * kRPW;       // rows per workgroup iteration
 };
 
-// Workspace layout: [BH][kDecodeMaxSplits][D + 2] floats (unnormalised out, max, sum),
-// then [BH] uint32 tickets.
-__host__ __device__ inline size_t decode_partial_floats(int BH, int D)
-{
-    return (size_t)BH * kDecodeMaxSplits * (size_t)(D + 2);
-}
-
-template <int DT, int D>
-__global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
+template <int DT, int D, int WAVES, int UNROLL>
+__global__ __launch_bounds__(WAVES * kWave) void decode_step_kernel(
     const uint4* __restrict__ q, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
-    uint4* k_cache, uint4* v_cache, int32_t* pos, uint4* __restrict__ out, float* ws_partial,
-    unsigned int* ws_ticket, int H, int G, int cap, int cache_len, int evict_idx, int32_t new_pos,
-    float scale_log2e, int rows_per_split, int n_splits)
+    uint4* k_cache, uint4* v_cache, int32_t* pos, uint4* __restrict__ out, int H, int G, int cap,
+    int cache_len, int evict_idx, int32_t new_pos, float scale_log2e)
 {
-    using S = DecodeShape<DT, D>;
-    constexpr int LPR = S::kLPR, RPW = S::kRPW, EPL = S::kEPL;
-    const int split = blockIdx.x;
-    const int bh = blockIdx.y;
+    using S = DecodeShape<DT, D, WAVES, UNROLL>;
+    constexpr int kDecodeUnroll = UNROLL;
+    constexpr int LPR = S::kLPR, RPW = S::kRPW, EPL = S::kEPL, THREADS = S::kThreads, TILE = S::kTile;
+    const int bh = blockIdx.x;
     const int tid = threadIdx.x;
     const int wave = tid / kWave;
     const int lane = tid % kWave;
@@ -55,13 +45,20 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
     const int rgrp = lane / LPR;  // which row of the wave's load
 
     const int n_rows = cache_len + 1;  // row cache_len is the new one, still in k_new/v_new
-    const int row_begin = split * rows_per_split;
-    const int row_end = min(n_rows, row_begin + rows_per_split);
+    const int n_tiles = (n_rows + TILE - 1) / TILE;
+    const int first_row = n_rows - n_tiles * TILE;  // <= 0: tile 0 is the ragged one
 
-    const uint4* kc = k_cache + (size_t)bh * cap * LPR;
-    const uint4* vc = v_cache + (size_t)bh * cap * LPR;
+    uint4* kc = k_cache + (size_t)bh * cap * LPR;
+    uint4* vc = v_cache + (size_t)bh * cap * LPR;
     const uint4* kn = k_new + (size_t)bh * LPR;
     const uint4* vn = v_new + (size_t)bh * LPR;
+
+    // positions of the rows behind the victim, fetched early (stored after the barrier)
+    const bool owns_pos = pos != nullptr && (G == H || (bh % H) == 0);
+    int32_t* pp = owns_pos ? pos + ((size_t)(bh / H) * G + (G == 1 ? 0 : bh % H)) * cap : nullptr;
+    const int n_move = (evict_idx >= 0) ? max(cache_len - 1 - evict_idx, 0) : 0;
+    int32_t pos_pref = 0;
+    if (owns_pos && tid < n_move) pos_pref = pp[evict_idx + 1 + tid];
 
     float qf[EPL];
     {
@@ -76,35 +73,41 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
-    for (int base = row_begin; base < row_end; base += S::kTile) {
-        uint4 kf[kDecodeUnroll], vf[kDecodeUnroll];
-        bool valid[kDecodeUnroll];
+    uint4 kf[kDecodeUnroll], vf[kDecodeUnroll], kf2[kDecodeUnroll], vf2[kDecodeUnroll];
+    const int lane_row = wave * RPW + rgrp;  // row offset of this lane group inside one unroll slab
+
+    auto load_tile = [&](int t, uint4* kd, uint4* vd) {
 #pragma unroll
         for (int u = 0; u < kDecodeUnroll; ++u) {
-            const int r = base + (u * kDecodeWaves + wave) * RPW + rgrp;
-            valid[u] = r < row_end;
-            const bool is_new = (r == cache_len);
-            const uint4* kp = is_new ? kn + sub : kc + (size_t)r * LPR + sub;
-            const uint4* vp = is_new ? vn + sub : vc + (size_t)r * LPR + sub;
-            if (valid[u]) {
-                kf[u] = *kp;
-                vf[u] = *vp;
+            const int r = first_row + t * TILE + u * (WAVES * RPW) + lane_row;
+            if (r >= 0) {
+                const bool is_new = (r == cache_len);
+                kd[u] = is_new ? kn[sub] : kc[(size_t)r * LPR + sub];
+                vd[u] = is_new ? vn[sub] : vc[(size_t)r * LPR + sub];
             } else {
-                kf[u] = make_uint4(0, 0, 0, 0);
-                vf[u] = make_uint4(0, 0, 0, 0);
+                kd[u] = make_uint4(0, 0, 0, 0);
+                vd[u] = make_uint4(0, 0, 0, 0);
             }
         }
+    };
+
+    load_tile(0, kf, vf);
+    for (int t = 0;; ++t) {
+        const bool more = t + 1 < n_tiles;
+        if (more) load_tile(t + 1, kf2, vf2);
+
         float s[kDecodeUnroll];
         float m_tile = -INFINITY;
 #pragma unroll
         for (int u = 0; u < kDecodeUnroll; ++u) {
+            const int r = first_row + t * TILE + u * (WAVES * RPW) + lane_row;
             float kx[EPL];
             unpack<DT>(kf[u], kx);
             float d = 0.f;
 #pragma unroll
             for (int e = 0; e < EPL; ++e) d = fmaf(qf[e], kx[e], d);
             d = group_sum<LPR>(d);
-            s[u] = valid[u] ? d : -INFINITY;
+            s[u] = (r >= 0) ? d : -INFINITY;
             m_tile = fmaxf(m_tile, s[u]);
         }
         const float m_new = fmaxf(m_run, m_tile);
@@ -124,76 +127,55 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
             }
             m_run = m_new;
         }
-    }
-
-    // ---- merge the row groups of this workgroup through LDS ----
-    __shared__ float sh_acc[S::kGroups][D];
-    __shared__ float sh_m[S::kGroups];
-    __shared__ float sh_l[S::kGroups];
-    __shared__ int sh_last;
-    const int grp = wave * RPW + rgrp;
+        if (!more) break;  // kf/vf keep the last tile: the newest rows
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) sh_acc[grp][sub * EPL + e] = acc[e];
-    if (sub == 0) {
-        sh_m[grp] = m_run;
-        sh_l[grp] = l_run;
+        for (int u = 0; u < kDecodeUnroll; ++u) {
+            kf[u] = kf2[u];
+            vf[u] = vf2[u];
+        }
     }
-    __syncthreads();
 
-    float* part = ws_partial + ((size_t)bh * kDecodeMaxSplits + split) * (D + 2);
-    float o_d = 0.f, M = -INFINITY, L = 0.f;
+    // ---- merge the RPW row groups of each wave with shuffles (lanes that hold the same chunk) ----
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) {
+        const float m_o = __shfl_xor(m_run, off, kWave);
+        const float l_o = __shfl_xor(l_run, off, kWave);
+        const float m_n = fmaxf(m_run, m_o);
+        const float w_s = (m_run > -INFINITY) ? exp2f(m_run - m_n) : 0.f;
+        const float w_o = (m_o > -INFINITY) ? exp2f(m_o - m_n) : 0.f;
+        l_run = l_run * w_s + l_o * w_o;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            const float a_o = __shfl_xor(acc[e], off, kWave);
+            acc[e] = acc[e] * w_s + a_o * w_o;
+        }
+        m_run = m_n;
+    }
+
+    // ---- merge the waves through LDS ----
+    __shared__ float sh_acc[WAVES][D];
+    __shared__ float sh_m[WAVES];
+    __shared__ float sh_l[WAVES];
+    if (rgrp == 0) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) sh_acc[wave][sub * EPL + e] = acc[e];
+        if (sub == 0) {
+            sh_m[wave] = m_run;
+            sh_l[wave] = l_run;
+        }
+    }
+    __syncthreads();  // also: every wave of this workgroup has finished reading the cache
+
     if (tid < D) {
+        float M = -INFINITY, L = 0.f, o_d = 0.f;
 #pragma unroll
-        for (int g = 0; g < S::kGroups; ++g) M = fmaxf(M, sh_m[g]);
+        for (int w = 0; w < WAVES; ++w) M = fmaxf(M, sh_m[w]);
 #pragma unroll
-        for (int g = 0; g < S::kGroups; ++g) {
-            const float w = (sh_m[g] > -INFINITY) ? exp2f(sh_m[g] - M) : 0.f;
-            L = fmaf(sh_l[g], w, L);
-            o_d = fmaf(sh_acc[g][tid], w, o_d);
+        for (int w = 0; w < WAVES; ++w) {
+            const float wt = (sh_m[w] > -INFINITY) ? exp2f(sh_m[w] - M) : 0.f;
+            L = fmaf(sh_l[w], wt, L);
+            o_d = fmaf(sh_acc[w][tid], wt, o_d);
         }
-    }
-
-    if (n_splits > 1) {
-        if (tid < D) {
-            part[tid] = o_d;
-            if (tid == 0) {
-                part[D] = M;
-                part[D + 1] = L;
-            }
-        }
-        __threadfence();  // partials visible device-wide before the ticket is taken
-        __syncthreads();
-        if (tid == 0) {
-            const unsigned int old = atomicInc(&ws_ticket[bh], (unsigned int)(n_splits - 1));
-            sh_last = (old == (unsigned int)(n_splits - 1));  // ticket wraps back to 0 for the next call
-        }
-        __syncthreads();
-        if (!sh_last) return;
-        __threadfence();
-        if (tid < D) {
-            const float* pb = ws_partial + (size_t)bh * kDecodeMaxSplits * (D + 2);
-            M = -INFINITY;
-            for (int sp = 0; sp < n_splits; ++sp)
-                M = fmaxf(M, __hip_atomic_load(pb + sp * (D + 2) + D, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT));
-            L = 0.f;
-            o_d = 0.f;
-            for (int sp = 0; sp < n_splits; ++sp) {
-                const float ms = __hip_atomic_load(pb + sp * (D + 2) + D, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-                const float ls = __hip_atomic_load(pb + sp * (D + 2) + D + 1, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-                const float os = __hip_atomic_load(pb + sp * (D + 2) + tid, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-                const float w = (ms > -INFINITY) ? exp2f(ms - M) : 0.f;
-                L = fmaf(ls, w, L);
-                o_d = fmaf(os, w, o_d);
-            }
-        }
-    }
-
-    // ---- write out[bh, :] ----
-    if (tid < D) {
         const float r = o_d / L;
         typename Elem<DT>::type* o = reinterpret_cast<typename Elem<DT>::type*>(out) + (size_t)bh * D;
         if constexpr (DT == EC_F32)
@@ -202,97 +184,111 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(
             o[tid] = f32_to_bf16(r);
     }
 
-    // ---- every reader of this (b,h) is done: evict (shift the tail up) and append ----
-    // Rows evict_idx+1 .. cache_len-1 of the cache move to evict_idx .. cache_len-2; the new row
-    // lands at cache_len-1 (eviction) or cache_len (none); it is dropped if it is the victim.
-    uint4* kcw = k_cache + (size_t)bh * cap * LPR;
-    uint4* vcw = v_cache + (size_t)bh * cap * LPR;
+    // ---- fixed-point elimination + append ----
+    // With a victim, rows evict_idx+1 .. cache_len (the last being the new row) move up by one; the
+    // new row is dropped if it is the victim itself.  Without one, the new row lands at cache_len.
+    const int last_tile_row0 = first_row + (n_tiles - 1) * TILE;  // first row still held in registers
     if (evict_idx >= 0) {
-        const int n_move = cache_len - 1 - evict_idx;  // rows taken from the cache itself
-        const int total = n_move * LPR;                // 16-byte chunks per tensor
-        for (int c0 = 0; c0 < total; c0 += kDecodeThreads) {
+        // rows behind the victim that left the registers long ago (only when more than a tile moves)
+        const int slow_end = min(last_tile_row0, cache_len);  // rows [evict_idx+1, slow_end) via memory
+        const int total = max(slow_end - (evict_idx + 1), 0) * LPR;
+        for (int c0 = 0; c0 < total; c0 += THREADS) {
             const int c = c0 + tid;
             uint4 kk, vv;
             if (c < total) {
-                kk = kcw[(size_t)(evict_idx + 1) * LPR + c];
-                vv = vcw[(size_t)(evict_idx + 1) * LPR + c];
+                kk = kc[(size_t)(evict_idx + 1) * LPR + c];
+                vv = vc[(size_t)(evict_idx + 1) * LPR + c];
             }
             __syncthreads();  // all reads of this slab before any write into it
             if (c < total) {
-                kcw[(size_t)evict_idx * LPR + c] = kk;
-                vcw[(size_t)evict_idx * LPR + c] = vv;
+                kc[(size_t)evict_idx * LPR + c] = kk;
+                vc[(size_t)evict_idx * LPR + c] = vv;
             }
         }
-    }
-    const int new_row = (evict_idx < 0) ? cache_len : ((evict_idx == cache_len) ? -1 : cache_len - 1);
-    if (new_row >= 0 && tid < 2 * LPR) {
-        if (tid < LPR)
-            kcw[(size_t)new_row * LPR + tid] = kn[tid];
-        else
-            vcw[(size_t)new_row * LPR + (tid - LPR)] = vn[tid - LPR];
+        if (total > 0) __syncthreads();
+#pragma unroll
+        for (int u = 0; u < kDecodeUnroll; ++u) {
+            const int r = last_tile_row0 + u * (WAVES * RPW) + lane_row;
+            if (r > evict_idx && r >= 0) {
+                kc[(size_t)(r - 1) * LPR + sub] = kf[u];
+                vc[(size_t)(r - 1) * LPR + sub] = vf[u];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < kDecodeUnroll; ++u) {
+            const int r = last_tile_row0 + u * (WAVES * RPW) + lane_row;
+            if (r == cache_len) {
+                kc[(size_t)r * LPR + sub] = kf[u];
+                vc[(size_t)r * LPR + sub] = vf[u];
+            }
+        }
     }
 
     // ---- positions: one copy per score group ----
-    if (pos != nullptr) {
-        const int b = bh / H, h = bh % H;
-        if (G == H || h == 0) {
-            int32_t* pp = pos + ((size_t)b * G + (G == 1 ? 0 : h)) * cap;
-            if (evict_idx >= 0) {
-                const int n_move = cache_len - 1 - evict_idx;
-                for (int c0 = 0; c0 < n_move; c0 += kDecodeThreads) {
-                    const int c = c0 + tid;
-                    int32_t pv = 0;
-                    if (c < n_move) pv = pp[evict_idx + 1 + c];
-                    __syncthreads();
-                    if (c < n_move) pp[evict_idx + c] = pv;
-                }
-            }
-            if (new_row >= 0 && tid == 0) pp[new_row] = new_pos;
+    if (owns_pos) {
+        if (tid < n_move) pp[evict_idx + tid] = pos_pref;  // fetched before the barrier above
+        for (int c0 = THREADS; c0 < n_move; c0 += THREADS) {  // beyond one workgroup's worth
+            const int c = c0 + tid;
+            int32_t pv = 0;
+            if (c < n_move) pv = pp[evict_idx + 1 + c];
+            __syncthreads();
+            if (c < n_move) pp[evict_idx + c] = pv;
         }
+        const int new_row = (evict_idx < 0) ? cache_len : ((evict_idx == cache_len) ? -1 : cache_len - 1);
+        if (new_row >= 0 && tid == 0) pp[new_row] = new_pos;
     }
 }
 
-template <int DT, int D>
-static int launch_decode(const void* q, const void* k_new, const void* v_new, void* k_cache,
-                         void* v_cache, int32_t* pos, int B, int H, int G, int cap, int cache_len,
-                         int evict_idx, int32_t new_pos, float scale, void* out, void* ws,
-                         int forced_splits, hipStream_t stream)
+template <int DT, int D, int WAVES, int UNROLL>
+static int launch_decode_w(const void* q, const void* k_new, const void* v_new, void* k_cache,
+                           void* v_cache, int32_t* pos, int B, int H, int G, int cap, int cache_len,
+                           int evict_idx, int32_t new_pos, float scale, void* out, hipStream_t stream)
 {
-    using S = DecodeShape<DT, D>;
-    const int BH = B * H;
-    const int n_rows = cache_len + 1;
-    const int max_by_rows = (n_rows + S::kTile - 1) / S::kTile;
-    int splits = forced_splits > 0 ? forced_splits : (1024 + BH - 1) / BH;
-    splits = max(1, min(min(splits, kDecodeMaxSplits), max_by_rows));
-    int rows_per_split = (n_rows + splits - 1) / splits;
-    rows_per_split = ((rows_per_split + S::kTile - 1) / S::kTile) * S::kTile;
-    splits = (n_rows + rows_per_split - 1) / rows_per_split;
-
-    float* ws_partial = reinterpret_cast<float*>(ws);
-    unsigned int* ws_ticket = reinterpret_cast<unsigned int*>(ws_partial + decode_partial_floats(BH, D));
-    dim3 grid(splits, BH);
-    hipLaunchKernelGGL((decode_step_kernel<DT, D>), grid, dim3(kDecodeThreads), 0, stream,
+    using S = DecodeShape<DT, D, WAVES, UNROLL>;
+    hipLaunchKernelGGL((decode_step_kernel<DT, D, WAVES, UNROLL>), dim3(B * H), dim3(S::kThreads), 0, stream,
                        (const uint4*)q, (const uint4*)k_new, (const uint4*)v_new, (uint4*)k_cache,
-                       (uint4*)v_cache, pos, (uint4*)out, ws_partial, ws_ticket, H, G, cap, cache_len,
-                       evict_idx, new_pos, scale * kLog2e, rows_per_split, splits);
+                       (uint4*)v_cache, pos, (uint4*)out, H, G, cap, cache_len, evict_idx, new_pos,
+                       scale * kLog2e);
     return status_from_hip(hipGetLastError());
 }
 
-size_t decode_workspace_bytes(int B, int H, int D)
+// Workgroup width and loads in flight grow with the number of rows to stream.
+template <int DT, int D>
+static int launch_decode(const void* q, const void* k_new, const void* v_new, void* k_cache,
+                         void* v_cache, int32_t* pos, int B, int H, int G, int cap, int cache_len,
+                         int evict_idx, int32_t new_pos, float scale, void* out, int forced_waves,
+                         int forced_unroll, hipStream_t stream)
 {
-    const int BH = B * H;
-    return decode_partial_floats(BH, D) * sizeof(float) + (size_t)BH * sizeof(unsigned int);
+    const int n_rows = cache_len + 1;
+    int waves = forced_waves, unroll = forced_unroll;
+    if (waves <= 0) waves = (n_rows >= 256) ? 16 : (n_rows >= 96 ? 8 : 4);
+    if (unroll <= 0) unroll = 4;
+#define EC_DECODE_W(W_, U_)                                                                              \
+    if (waves == W_ && unroll == U_)                                                                     \
+        return launch_decode_w<DT, D, W_, U_>(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, cap, cache_len, \
+                                              evict_idx, new_pos, scale, out, stream);
+    EC_DECODE_W(4, 4)
+    EC_DECODE_W(8, 4)
+    EC_DECODE_W(16, 4)
+    EC_DECODE_W(16, 6)
+    EC_DECODE_W(8, 8)
+    EC_DECODE_W(8, 12)
+    EC_DECODE_W(4, 12)
+#undef EC_DECODE_W
+    return EC_EINVAL;
 }
 
 int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                     int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
-                    int32_t new_pos, float scale, int dt, void* out, void* ws, int forced_splits,
+                    int32_t new_pos, float scale, int dt, void* out, int forced_waves, int forced_unroll,
                     hipStream_t stream)
 {
-#define EC_DECODE_CASE(DT_, D_)                                                                     \
-    if (dt == DT_ && D == D_)                                                                       \
-        return launch_decode<DT_, D_>(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, cap, cache_len, \
-                                      evict_idx, new_pos, scale, out, ws, forced_splits, stream);
+#define EC_DECODE_CASE(DT_, D_)                                                                       \
+    if (dt == DT_ && D == D_)                                                                         \
+        return launch_decode<DT_, D_>(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, cap, cache_len,    \
+                                      evict_idx, new_pos, scale, out, forced_waves,       \
+                                      forced_unroll, stream);
     EC_DECODE_CASE(EC_BF16, 128)
     EC_DECODE_CASE(EC_BF16, 64)
     EC_DECODE_CASE(EC_F32, 128)

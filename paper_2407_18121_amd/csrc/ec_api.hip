@@ -5,10 +5,9 @@
 #include "ec_common.h"
 
 namespace ec {
-size_t decode_workspace_bytes(int B, int H, int D);
 int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                     int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
-                    int32_t new_pos, float scale, int dt, void* out, void* ws, int forced_splits,
+                    int32_t new_pos, float scale, int dt, void* out, int forced_waves, int forced_unroll,
                     hipStream_t stream);
 int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G, int T,
                    int D, int n_anchor, int dt, void* k_cache, void* v_cache, int cap, int32_t* counts,
@@ -19,8 +18,9 @@ int score_simt_dispatch(const void* q, const void* k, const void* v, void* out, 
                         float* head_imp, int B, int H, int T, int D, int dt, float scale,
                         hipStream_t stream);
 int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
-                        float* head_imp, int B, int H, int T, int D, int dt, float scale,
+                        float* head_imp, void* vt, int B, int H, int T, int D, int dt, float scale,
                         hipStream_t stream);
+size_t score_mfma_vt_bytes(int B, int H, int T, int D);
 int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, hipStream_t stream);
 }  // namespace ec
 
@@ -59,13 +59,14 @@ size_t ec_workspace_bytes(int fn, int B, int H, int T, int D, int dt)
     switch (fn) {
         case EC_FN_PREFILL_SCORE:
             if (!shape_supported(D, dt)) return (size_t)-1;
-            // per-head importance [B,H,T] + row log-sum-exp [B,H,T], fp32
-            return 2 * align256((size_t)B * H * T * sizeof(float));
+            // per-head importance [B,H,T] + row log-sum-exp [B,H,T], fp32; bf16 adds a V^T copy
+            return 2 * align256((size_t)B * H * T * sizeof(float)) +
+                   (dt == EC_BF16 ? align256(ec::score_mfma_vt_bytes(B, H, T, D)) : 0);
         case EC_FN_SELECT_ANCHORS: return 0;
         case EC_FN_MERGE_COMPACT: return 0;
         case EC_FN_DECODE_STEP:
             if (!shape_supported(D, dt)) return (size_t)-1;
-            return align256(ec::decode_workspace_bytes(B, H, D));
+            return 0;  // one workgroup owns a whole (batch, head): nothing is staged in memory
         default: return (size_t)-1;
     }
 }
@@ -84,15 +85,17 @@ int ec_prefill_score(const void* q, const void* k, const void* v, void* out, flo
     if (!ws || ws_bytes < need) return EC_EWORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
 
+    const size_t stat_bytes = align256((size_t)B * H * T * sizeof(float));
     float* ws_imp = reinterpret_cast<float*>(ws);
-    float* ws_lse = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + need / 2);
+    float* ws_lse = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + stat_bytes);
+    void* ws_vt = reinterpret_cast<char*>(ws) + 2 * stat_bytes;
     float* lse_buf = lse ? lse : ws_lse;
     float* head_imp = (G == H) ? score : ws_imp;
 
     int rc;
     const bool use_mfma = (dt == EC_BF16) && !env_int("EC_SCORE_FORCE_SIMT", 0);
     if (use_mfma)
-        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, B, H, T, D, dt, scale, s);
+        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, ws_vt, B, H, T, D, dt, scale, s);
     else
         rc = ec::score_simt_dispatch(q, k, v, out, lse_buf, head_imp, B, H, T, D, dt, scale, s);
     if (rc != EC_OK) return rc;
@@ -169,10 +172,10 @@ int ec_decode_step(const void* q, const void* k_new, const void* v_new, void* k_
     if (!(scale == scale)) return EC_EINVAL;
     if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
     if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
-    const size_t need = ec_workspace_bytes(EC_FN_DECODE_STEP, B, H, cap, D, dt);
-    if (!ws || ws_bytes < need) return EC_EWORKSPACE;
+    (void)ws;
+    (void)ws_bytes;
     return ec::decode_dispatch(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, D, cap, cache_len, evict_idx,
-                               new_pos, scale, dt, out, ws, env_int("EC_DECODE_SPLITS", 0),
+                               new_pos, scale, dt, out, env_int("EC_DECODE_WAVES", 0), env_int("EC_DECODE_UNROLL", 0),
                                reinterpret_cast<hipStream_t>(stream));
 }
 

@@ -1,15 +1,315 @@
-// ec_prefill_score, matrix-core path for bf16 inputs (placeholder: forwards to the vector-ALU path).
+// ec_prefill_score, matrix-core path for bf16 inputs (Sec. 3.3, Eq. 1 and I_n = sum_m A_mn).
+//
+// Three kernels, none of which stores the T x T matrix:
+//   vt_transpose : V [T,D] -> V^T [D,Tp] per head (zero-padded to a multiple of 64 keys), so that
+//                  the contraction index of P.V is contiguous in memory for the MFMA operands.
+//   attn_fwd     : one workgroup = 128 queries (4 waves x 32), key tiles of 64 streamed through
+//                  LDS.  The score tile is computed TRANSPOSED, S^T = K.Q^T, with
+//                  v_mfma_f32_32x32x16_bf16: in the accumulator layout a lane then owns one query
+//                  (column) and 16 keys (rows), so the row max / row sum of the online softmax are
+//                  in-lane reductions plus one exchange between the two half-waves, the rescale
+//                  factor is a per-lane scalar, and the fp32 accumulators -- rounded to bf16 -- are
+//                  directly the B operand of O^T += V^T.P^T (the contraction index is permuted the
+//                  same way on both operands).  Emits out (optional) and the row log-sum-exp.
+//   colsum       : one workgroup = 128 keys (4 waves x 32) whose K fragments stay in registers;
+//                  query tiles of 64 at or below the diagonal are streamed through LDS, S = Q.K^T
+//                  is recomputed un-transposed so that a lane owns one key (column): p =
+//                  exp(s - lse_row) is summed down the column in-lane.  One workgroup owns a column,
+//                  so there are no atomics and the result is deterministic.
+//
+// MFMA operand layout used throughout (wave64, lane l, half h = l / 32):
+//   A (32 x 16): lane holds A[l % 32][8h .. 8h+7]      B (16 x 32): lane holds B[8h .. 8h+7][l % 32]
+//   C (32 x 32): lane holds C[8g + 4h + t][l % 32] in register 4g + t, g,t in 0..3
 #include "ec_common.h"
 
 namespace ec {
-int score_simt_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
-                        float* head_imp, int B, int H, int T, int D, int dt, float scale,
-                        hipStream_t stream);
 
-int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
-                        float* head_imp, int B, int H, int T, int D, int dt, float scale,
-                        hipStream_t stream)
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kMfmaThreads = 256;
+constexpr int kFwdBM = 128;  // queries per workgroup (32 per wave)
+constexpr int kFwdBN = 64;   // keys per LDS tile
+constexpr int kColBN = 128;  // keys per workgroup in colsum (32 per wave)
+constexpr int kColBM = 64;   // queries per LDS tile in colsum
+constexpr int kVtPitch = kFwdBN + 4;  // bf16 elements per V^T row in LDS (136 B: conflict-free b64 reads)
+
+__host__ __device__ inline int padded_T(int T) { return (T + 63) / 64 * 64; }
+
+// ------------------------------------------------------------------ V^T
+__global__ __launch_bounds__(256) void vt_transpose_kernel(const uint16_t* __restrict__ v,
+                                                           uint16_t* __restrict__ vt, int T, int Tp, int D)
 {
-    return score_simt_dispatch(q, k, v, out, lse, head_imp, B, H, T, D, dt, scale, stream);
+    __shared__ uint16_t tile[64][64 + 2];
+    const int bh = blockIdx.z;
+    const int n0 = blockIdx.x * 64, d0 = blockIdx.y * 64;
+    const uint16_t* src = v + (size_t)bh * T * D;
+    uint16_t* dst = vt + (size_t)bh * D * Tp;
+    for (int i = threadIdx.x; i < 64 * 32; i += 256) {  // pairs of elements along d
+        const int r = i / 32, c = (i % 32) * 2;
+        uint32_t x = 0;
+        if (n0 + r < T) x = *reinterpret_cast<const uint32_t*>(src + (size_t)(n0 + r) * D + d0 + c);
+        tile[r][c] = (uint16_t)(x & 0xffffu);
+        tile[r][c + 1] = (uint16_t)(x >> 16);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * 32; i += 256) {  // pairs of elements along n
+        const int d = i / 32, c = (i % 32) * 2;
+        const uint32_t x = (uint32_t)tile[c][d] | ((uint32_t)tile[c + 1][d] << 16);
+        *reinterpret_cast<uint32_t*>(dst + (size_t)(d0 + d) * Tp + n0 + c) = x;
+    }
 }
+
+// ------------------------------------------------------------------ forward
+template <int D>
+__global__ __launch_bounds__(kMfmaThreads) void attn_fwd_mfma_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
+    uint16_t* __restrict__ out, float* __restrict__ lse, int T, int Tp, float scale_log2e)
+{
+    constexpr int KB = D / 16;       // contraction blocks of Q.K
+    constexpr int DB = D / 32;       // 32-row blocks of O^T
+    constexpr int KP = D + 8;        // K tile pitch in elements (272 B for D=128: conflict-free b128)
+    __shared__ __align__(16) uint16_t ks[kFwdBN * KP];
+    __shared__ __align__(16) uint16_t vs[D * kVtPitch];
+
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int c32 = lane % 32, h = lane / 32;
+    const int bh = blockIdx.y;
+    const int m0 = (gridDim.x - 1 - blockIdx.x) * kFwdBM;  // longest rows first
+    const int m = m0 + wave * 32 + c32;                    // this lane's query
+    const uint16_t* qh = q + (size_t)bh * T * D;
+    const uint16_t* kh = k + (size_t)bh * T * D;
+    const uint16_t* vth = vt + (size_t)bh * D * Tp;
+    const bool want_out = out != nullptr;
+
+    bf16x8 qf[KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+        uint4 x = make_uint4(0, 0, 0, 0);
+        if (m < T) x = *reinterpret_cast<const uint4*>(qh + (size_t)m * D + kb * 16 + h * 8);
+        qf[kb] = __builtin_bit_cast(bf16x8, x);
+    }
+
+    f32x16 o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;  // l_run: this half-wave's share of the row sum
+
+    const int n_end = min(T, m0 + kFwdBM);
+    for (int n0 = 0; n0 < n_end; n0 += kFwdBN) {
+        __syncthreads();  // previous tile fully consumed
+        for (int c = tid; c < kFwdBN * (D / 8); c += kMfmaThreads) {
+            const int r = c / (D / 8), cc = c % (D / 8);
+            uint4 x = make_uint4(0, 0, 0, 0);
+            if (n0 + r < T) x = *reinterpret_cast<const uint4*>(kh + (size_t)(n0 + r) * D + cc * 8);
+            *reinterpret_cast<uint4*>(&ks[r * KP + cc * 8]) = x;
+        }
+        if (want_out) {
+            for (int c = tid; c < D * (kFwdBN / 8); c += kMfmaThreads) {
+                const int d = c / (kFwdBN / 8), cc = c % (kFwdBN / 8);
+                const uint4 x = *reinterpret_cast<const uint4*>(vth + (size_t)d * Tp + n0 + cc * 8);
+                uint2* dst = reinterpret_cast<uint2*>(&vs[d * kVtPitch + cc * 8]);
+                dst[0] = make_uint2(x.x, x.y);
+                dst[1] = make_uint2(x.z, x.w);
+            }
+        }
+        __syncthreads();
+
+        // S^T = K . Q^T : two 32-key blocks x this wave's 32 queries
+        f32x16 s[2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ks[(nb * 32 + c32) * KP + kb * 16 + h * 8]);
+                s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kb], s[nb], 0, 0, 0);
+            }
+        }
+        // scale, causal mask, row max
+        float mx = -INFINITY;
+        const bool diag = (n0 + kFwdBN - 1 > m0 + wave * 32) || (n0 + kFwdBN > T);
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float x = s[nb][r] * scale_log2e;
+                if (diag) {
+                    const int n = n0 + nb * 32 + (r / 4) * 8 + h * 4 + (r % 4);
+                    if (n > m || n >= T) x = -INFINITY;
+                }
+                s[nb][r] = x;
+                mx = fmaxf(mx, x);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every query
+        const float corr = exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(s[nb][r] - m_new);
+                s[nb][r] = p;
+                psum += p;
+            }
+        l_run = l_run * corr + psum;
+
+        if (want_out) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[db][r] *= corr;
+            // O^T += V^T . P^T, 16 keys per MFMA; slot s of half h <-> key 8g + 4h + s (g = g0, g0+1)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int nb = kk / 2, g0 = (kk % 2) * 2;
+                bf16x8 pf;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    pf[t] = (__bf16)s[nb][g0 * 4 + t];
+                    pf[4 + t] = (__bf16)s[nb][(g0 + 1) * 4 + t];
+                }
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const uint16_t* row = &vs[(db * 32 + c32) * kVtPitch + nb * 32 + h * 4];
+                    const uint2 lo = *reinterpret_cast<const uint2*>(row + g0 * 8);
+                    const uint2 hi = *reinterpret_cast<const uint2*>(row + (g0 + 1) * 8);
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, o[db], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+    if (m < T) {
+        if (h == 0) lse[(size_t)bh * T + m] = (m_run + log2f(l_tot)) * kLn2;
+        if (want_out) {
+            const float inv = 1.f / l_tot;
+            uint16_t* orow = out + ((size_t)bh * T + m) * D;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 y;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) y[t] = (__bf16)(o[db][g * 4 + t] * inv);
+                    *reinterpret_cast<bf16x4*>(orow + db * 32 + g * 8 + h * 4) = y;
+                }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ column mass
+template <int D>
+__global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const float* __restrict__ lse,
+    float* __restrict__ head_imp, int T, float scale_log2e)
+{
+    constexpr int KB = D / 16;
+    constexpr int QP = D + 8;
+    __shared__ __align__(16) uint16_t qs[kColBM * QP];
+    __shared__ __align__(16) float lse2[kColBM];  // row log-sum-exp in base-2 units
+
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int c32 = lane % 32, h = lane / 32;
+    const int bh = blockIdx.y;
+    const int n0 = blockIdx.x * kColBN;  // low key tiles (most query tiles) are scheduled first
+    const int n = n0 + wave * 32 + c32;  // this lane's key
+    const uint16_t* qh = q + (size_t)bh * T * D;
+    const uint16_t* kh = k + (size_t)bh * T * D;
+    const float* lh = lse + (size_t)bh * T;
+
+    bf16x8 kf[KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+        uint4 x = make_uint4(0, 0, 0, 0);
+        if (n < T) x = *reinterpret_cast<const uint4*>(kh + (size_t)n * D + kb * 16 + h * 8);
+        kf[kb] = __builtin_bit_cast(bf16x8, x);
+    }
+
+    float col = 0.f;
+    for (int m0 = (n0 / kColBM) * kColBM; m0 < T; m0 += kColBM) {
+        __syncthreads();
+        for (int c = tid; c < kColBM * (D / 8); c += kMfmaThreads) {
+            const int r = c / (D / 8), cc = c % (D / 8);
+            uint4 x = make_uint4(0, 0, 0, 0);
+            if (m0 + r < T) x = *reinterpret_cast<const uint4*>(qh + (size_t)(m0 + r) * D + cc * 8);
+            *reinterpret_cast<uint4*>(&qs[r * QP + cc * 8]) = x;
+        }
+        if (tid < kColBM) lse2[tid] = (m0 + tid < T) ? lh[m0 + tid] * kLog2e : INFINITY;
+        __syncthreads();
+        if (m0 + kColBM - 1 < n0 + wave * 32) continue;  // every query of the tile precedes this wave's keys
+
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            f32x16 s;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&qs[(mb * 32 + c32) * QP + kb * 16 + h * 8]);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[kb], s, 0, 0, 0);
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 l4 = *reinterpret_cast<const float4*>(&lse2[mb * 32 + g * 8 + h * 4]);
+                const float lr[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int mm = m0 + mb * 32 + g * 8 + h * 4 + t;
+                    const float p = __builtin_amdgcn_exp2f(s[g * 4 + t] * scale_log2e - lr[t]);
+                    col += (mm >= n) ? p : 0.f;  // rows beyond T carry lse = +inf, so p = 0
+                }
+            }
+        }
+    }
+    col += __shfl_xor(col, 32, kWave);
+    if (h == 0 && n < T) head_imp[(size_t)bh * T + n] = col;
+}
+
+template <int D>
+static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse,
+                       float* head_imp, uint16_t* vt, int B, int H, int T, float scale, hipStream_t stream)
+{
+    const float sl = scale * kLog2e;
+    const int Tp = padded_T(T);
+    const int BH = B * H;
+    if (out != nullptr) {
+        hipLaunchKernelGGL(vt_transpose_kernel, dim3(Tp / 64, D / 64, BH), dim3(256), 0, stream, v, vt, T, Tp, D);
+        int rc = status_from_hip(hipGetLastError());
+        if (rc != EC_OK) return rc;
+    }
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D>), dim3((T + kFwdBM - 1) / kFwdBM, BH), dim3(kMfmaThreads), 0,
+                       stream, q, k, vt, out, lse, T, Tp, sl);
+    int rc = status_from_hip(hipGetLastError());
+    if (rc != EC_OK) return rc;
+    hipLaunchKernelGGL((colsum_mfma_kernel<D>), dim3((T + kColBN - 1) / kColBN, BH), dim3(kMfmaThreads), 0,
+                       stream, q, k, lse, head_imp, T, sl);
+    return status_from_hip(hipGetLastError());
+}
+
+// bytes of workspace the V^T copy needs
+size_t score_mfma_vt_bytes(int B, int H, int T, int D) { return (size_t)B * H * D * padded_T(T) * sizeof(uint16_t); }
+
+// Per-head importance into head_imp [B,H,T]; out may be NULL (then vt is not touched).
+int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse, float* head_imp,
+                        void* vt, int B, int H, int T, int D, int dt, float scale, hipStream_t stream)
+{
+    if (dt != EC_BF16) return EC_EUNSUPPORTED;
+    if (D == 128)
+        return launch_mfma<128>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out, lse,
+                                head_imp, (uint16_t*)vt, B, H, T, scale, stream);
+    if (D == 64)
+        return launch_mfma<64>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out, lse,
+                               head_imp, (uint16_t*)vt, B, H, T, scale, stream);
+    return EC_EUNSUPPORTED;
+}
+
 }  // namespace ec

@@ -136,17 +136,22 @@ def prompt_qkv(cfg: Config, layer: int = 0, batch=None):
     return (round_to_dtype(q, cfg.dtype), round_to_dtype(k, cfg.dtype), round_to_dtype(v, cfg.dtype))
 
 
-def decode_qkv(cfg: Config, layer: int, step: int, batch=None):
-    """Per-step q, k_new, v_new as fp32 arrays [len(batch),H,D] exact in cfg.dtype."""
+def decode_stream(cfg: Config, layer: int, batch=None):
+    """All per-step decode vectors of one layer: q, k_new, v_new as fp32 [steps,len(batch),H,D] exact in cfg.dtype."""
     bs = list(range(cfg.B)) if batch is None else list(batch)
-    shape = (cfg.H, cfg.D)
+    shape = (cfg.decode_steps, cfg.H, cfg.D)
     out = []
     for name in ("dq", "dk", "dv"):
-        a = np.empty((len(bs),) + shape, np.float32)
+        a = np.empty((cfg.decode_steps, len(bs), cfg.H, cfg.D), np.float32)
         for j, b in enumerate(bs):
-            a[j] = _rng(cfg, layer, name, b, step).standard_normal(shape, dtype=np.float32)
+            a[:, j] = _rng(cfg, layer, name, b).standard_normal(shape, dtype=np.float32)
         out.append(round_to_dtype(a, cfg.dtype))
     return tuple(out)
+
+
+def decode_qkv(cfg: Config, layer: int, step: int, batch=None):
+    """Per-step q, k_new, v_new as fp32 arrays [len(batch),H,D] exact in cfg.dtype."""
+    return tuple(a[step] for a in decode_stream(cfg, layer, batch))
 
 
 def custom(name: str, *, H: int, D: int, B: int, T: int, dtype: str, gamma=(1, 2), decode_steps=8,

@@ -28,7 +28,7 @@ def test_status_strings_and_workspace_sizes():
     assert ec.ec_workspace_bytes(ec.EC_FN_SELECT_ANCHORS, 1, 1, 16, 64, ec.EC_F32) == 0
     n = ec.ec_workspace_bytes(ec.EC_FN_PREFILL_SCORE, 2, 4, 100, 64, ec.EC_F32)
     assert n >= 2 * 2 * 4 * 100 * 4 and n % 256 == 0
-    assert ec.ec_workspace_bytes(ec.EC_FN_DECODE_STEP, 2, 4, 100, 128, ec.EC_BF16) > 0
+    assert ec.ec_workspace_bytes(ec.EC_FN_DECODE_STEP, 2, 4, 100, 128, ec.EC_BF16) == 0
     with pytest.raises(ec.EcError):
         ec.ec_workspace_bytes(ec.EC_FN_DECODE_STEP, 2, 4, 100, 96, ec.EC_BF16)
 
@@ -46,7 +46,7 @@ def test_invalid_arguments_are_rejected_before_any_launch():
     assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 64, 8, 8, -1, 0, 1.0, 0, one, one, 1 << 20, None) == ec.EC_EINVAL  # full
     assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 64, 8, 3, 4, 0, 1.0, 0, one, one, 1 << 20, None) == ec.EC_EINVAL   # evict > len
     assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 96, 8, 3, 1, 0, 1.0, 0, one, one, 1 << 20, None) == ec.EC_EUNSUPPORTED
-    assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 64, 8, 3, 1, 0, 1.0, 0, one, one, 16, None) == ec.EC_EWORKSPACE
+    assert lib.ec_prefill_score(one, one, one, None, None, one, 1, 1, 1, 8, 64, 0, 1.0, one, 16, None) == ec.EC_EWORKSPACE
     assert lib.ec_merge_compact(one, one, one, 1, 4, 2, 8, 64, 4, 0, one, one, 4, None, None, None, None) == ec.EC_EINVAL  # G not in {1,H}
 
 

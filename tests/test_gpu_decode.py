@@ -45,8 +45,6 @@ def _case(dtype, D, B, H, G, cap, cache_len, evict_idx, seed, scale=None):
     np.testing.assert_array_equal(to_host(dvc)[:, :, :n_after], ovc[:, :, :n_after])
     np.testing.assert_array_equal(dpos.cpu().numpy()[:, :, :n_after], opos[:, :, :n_after])
     assert (to_host(dkc)[:, :, cache_len + 1:] == 0).all() and (dpos.cpu().numpy()[:, :, cache_len + 1:] == -7).all()
-    assert int(ws.view(torch.int32).abs().sum()) >= 0  # ws readable
-    return ws
 
 
 @pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
@@ -64,15 +62,16 @@ def test_decode_step_shapes(dtype, D, B, H, G, cap, cache_len, evict_idx):
     _case(dtype, D, B, H, G, cap, cache_len, evict_idx, seed=cache_len * 7 + D)
 
 
-@pytest.mark.parametrize("splits", [1, 2, 5, 64])
-def test_decode_step_split_counts(splits, monkeypatch):
-    monkeypatch.setenv("EC_DECODE_SPLITS", str(splits))
-    _case("bf16", 128, 2, 3, 1, 900, 777, 777 - 25, seed=splits)
-    _case("f32", 64, 1, 4, 4, 900, 130, 3, seed=splits + 100)
+@pytest.mark.parametrize("waves", [4, 8, 16])
+def test_decode_step_workgroup_widths(waves, monkeypatch):
+    monkeypatch.setenv("EC_DECODE_WAVES", str(waves))
+    _case("bf16", 128, 2, 3, 1, 900, 777, 777 - 25, seed=waves)
+    _case("f32", 64, 1, 4, 4, 900, 130, 3, seed=waves + 100)     # more than one tile moves
+    _case("bf16", 64, 1, 2, 2, 900, 511, 511, seed=waves + 200)  # victim = new row, full tiles
+    _case("f32", 128, 1, 2, 1, 900, 512, 1, seed=waves + 300)
 
 
-def test_ticket_wraps_so_workspace_is_reusable():
-    # same workspace, several calls in a row with different split counts
+def test_back_to_back_calls_of_different_lengths():
     B, H, D, cap, dtype = 2, 4, 128, 600, "bf16"
     rng = np.random.default_rng(3)
     ws = ec.new_workspace(ec.EC_FN_DECODE_STEP, B, H, cap, D, ec.EC_BF16)
@@ -89,7 +88,6 @@ def test_ticket_wraps_so_workspace_is_reusable():
                           None, cache_len, -1, 0, 0.1, dout, ws, G=1)
         torch.cuda.synchronize()
         assert_close(to_host(dout), oout, dtype, f"out@{cache_len}")
-    assert int(ws[-B * H * 4 - 256:].view(torch.int32).abs().sum()) == 0 or True
 
 
 def test_generation_run_tiny_config():
