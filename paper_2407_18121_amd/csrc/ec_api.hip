@@ -19,7 +19,7 @@ int score_simt_dispatch(const void* q, const void* k, const void* v, void* out, 
                         hipStream_t stream);
 int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
                         float* head_imp, void* vt, int B, int H, int T, int D, int dt, float scale,
-                        hipStream_t stream);
+                        int forced_waves, hipStream_t stream);
 size_t score_mfma_vt_bytes(int B, int H, int T, int D);
 int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, hipStream_t stream);
 }  // namespace ec
@@ -95,7 +95,8 @@ int ec_prefill_score(const void* q, const void* k, const void* v, void* out, flo
     int rc;
     const bool use_mfma = (dt == EC_BF16) && !env_int("EC_SCORE_FORCE_SIMT", 0);
     if (use_mfma)
-        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, ws_vt, B, H, T, D, dt, scale, s);
+        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, ws_vt, B, H, T, D, dt, scale,
+                                     env_int("EC_SCORE_WAVES", 0), s);
     else
         rc = ec::score_simt_dispatch(q, k, v, out, lse_buf, head_imp, B, H, T, D, dt, scale, s);
     if (rc != EC_OK) return rc;

@@ -29,7 +29,6 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kMfmaThreads = 256;
-constexpr int kFwdBM = 128;  // queries per workgroup (32 per wave)
 constexpr int kFwdBN = 64;   // keys per LDS tile
 constexpr int kColBN = 128;  // keys per workgroup in colsum (32 per wave)
 constexpr int kColBM = 64;   // queries per LDS tile in colsum
@@ -62,22 +61,30 @@ __global__ __launch_bounds__(256) void vt_transpose_kernel(const uint16_t* __res
 }
 
 // ------------------------------------------------------------------ forward
-template <int D>
-__global__ __launch_bounds__(kMfmaThreads) void attn_fwd_mfma_kernel(
+// Double-buffered: the global loads of key tile i+1 are issued before tile i is consumed and land
+// in the other LDS buffer after it, so there is one barrier per tile and the HBM/L2 latency is
+// hidden behind the MFMA + softmax work of the current tile.
+template <int D, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     uint16_t* __restrict__ out, float* __restrict__ lse, int T, int Tp, float scale_log2e)
 {
+    constexpr int THREADS = WAVES * kWave;
+    constexpr int BM = WAVES * 32;   // queries per workgroup
     constexpr int KB = D / 16;       // contraction blocks of Q.K
     constexpr int DB = D / 32;       // 32-row blocks of O^T
     constexpr int KP = D + 8;        // K tile pitch in elements (272 B for D=128: conflict-free b128)
-    __shared__ __align__(16) uint16_t ks[kFwdBN * KP];
-    __shared__ __align__(16) uint16_t vs[D * kVtPitch];
+    constexpr int KCH = kFwdBN * (D / 8) / THREADS;  // 16-byte chunks of the K tile per thread
+    constexpr int VCH = D * (kFwdBN / 8) / THREADS;  // 16-byte chunks of the V^T tile per thread
+    __shared__ __align__(16) uint16_t ks[2][kFwdBN * KP];
+    __shared__ __align__(16) uint16_t vs[2][D * kVtPitch];
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int c32 = lane % 32, h = lane / 32;
     const int bh = blockIdx.y;
-    const int m0 = (gridDim.x - 1 - blockIdx.x) * kFwdBM;  // longest rows first
-    const int m = m0 + wave * 32 + c32;                    // this lane's query
+    const int m0 = (gridDim.x - 1 - blockIdx.x) * BM;  // longest rows first
+    const int mw = m0 + wave * 32;                     // first query of this wave
+    const int m = mw + c32;                            // this lane's query
     const uint16_t* qh = q + (size_t)bh * T * D;
     const uint16_t* kh = k + (size_t)bh * T * D;
     const uint16_t* vth = vt + (size_t)bh * D * Tp;
@@ -98,93 +105,156 @@ __global__ __launch_bounds__(kMfmaThreads) void attn_fwd_mfma_kernel(
         for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;  // l_run: this half-wave's share of the row sum
 
-    const int n_end = min(T, m0 + kFwdBM);
-    for (int n0 = 0; n0 < n_end; n0 += kFwdBN) {
-        __syncthreads();  // previous tile fully consumed
-        for (int c = tid; c < kFwdBN * (D / 8); c += kMfmaThreads) {
+    uint4 kreg[KCH], vreg[VCH];
+    auto fetch = [&](int n0) {
+#pragma unroll
+        for (int i = 0; i < KCH; ++i) {
+            const int c = tid + i * THREADS;
             const int r = c / (D / 8), cc = c % (D / 8);
-            uint4 x = make_uint4(0, 0, 0, 0);
-            if (n0 + r < T) x = *reinterpret_cast<const uint4*>(kh + (size_t)(n0 + r) * D + cc * 8);
-            *reinterpret_cast<uint4*>(&ks[r * KP + cc * 8]) = x;
+            kreg[i] = make_uint4(0, 0, 0, 0);
+            if (n0 + r < T) kreg[i] = *reinterpret_cast<const uint4*>(kh + (size_t)(n0 + r) * D + cc * 8);
         }
         if (want_out) {
-            for (int c = tid; c < D * (kFwdBN / 8); c += kMfmaThreads) {
+#pragma unroll
+            for (int i = 0; i < VCH; ++i) {
+                const int c = tid + i * THREADS;
                 const int d = c / (kFwdBN / 8), cc = c % (kFwdBN / 8);
-                const uint4 x = *reinterpret_cast<const uint4*>(vth + (size_t)d * Tp + n0 + cc * 8);
-                uint2* dst = reinterpret_cast<uint2*>(&vs[d * kVtPitch + cc * 8]);
-                dst[0] = make_uint2(x.x, x.y);
-                dst[1] = make_uint2(x.z, x.w);
+                vreg[i] = *reinterpret_cast<const uint4*>(vth + (size_t)d * Tp + n0 + cc * 8);
             }
         }
-        __syncthreads();
-
-        // S^T = K . Q^T : two 32-key blocks x this wave's 32 queries
-        f32x16 s[2];
+    };
+    auto stage = [&](int buf) {
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ks[(nb * 32 + c32) * KP + kb * 16 + h * 8]);
-                s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kb], s[nb], 0, 0, 0);
-            }
+        for (int i = 0; i < KCH; ++i) {
+            const int c = tid + i * THREADS;
+            const int r = c / (D / 8), cc = c % (D / 8);
+            *reinterpret_cast<uint4*>(&ks[buf][r * KP + cc * 8]) = kreg[i];
         }
-        // scale, causal mask, row max
-        float mx = -INFINITY;
-        const bool diag = (n0 + kFwdBN - 1 > m0 + wave * 32) || (n0 + kFwdBN > T);
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float x = s[nb][r] * scale_log2e;
-                if (diag) {
-                    const int n = n0 + nb * 32 + (r / 4) * 8 + h * 4 + (r % 4);
-                    if (n > m || n >= T) x = -INFINITY;
-                }
-                s[nb][r] = x;
-                mx = fmaxf(mx, x);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every query
-        const float corr = exp2f(m_run - m_new);
-        m_run = m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(s[nb][r] - m_new);
-                s[nb][r] = p;
-                psum += p;
-            }
-        l_run = l_run * corr + psum;
-
         if (want_out) {
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[db][r] *= corr;
-            // O^T += V^T . P^T, 16 keys per MFMA; slot s of half h <-> key 8g + 4h + s (g = g0, g0+1)
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int nb = kk / 2, g0 = (kk % 2) * 2;
-                bf16x8 pf;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    pf[t] = (__bf16)s[nb][g0 * 4 + t];
-                    pf[4 + t] = (__bf16)s[nb][(g0 + 1) * 4 + t];
-                }
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const uint16_t* row = &vs[(db * 32 + c32) * kVtPitch + nb * 32 + h * 4];
-                    const uint2 lo = *reinterpret_cast<const uint2*>(row + g0 * 8);
-                    const uint2 hi = *reinterpret_cast<const uint2*>(row + (g0 + 1) * 8);
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, o[db], 0, 0, 0);
-                }
+            for (int i = 0; i < VCH; ++i) {
+                const int c = tid + i * THREADS;
+                const int d = c / (kFwdBN / 8), cc = c % (kFwdBN / 8);
+                uint2* dst = reinterpret_cast<uint2*>(&vs[buf][d * kVtPitch + cc * 8]);
+                dst[0] = make_uint2(vreg[i].x, vreg[i].y);
+                dst[1] = make_uint2(vreg[i].z, vreg[i].w);
             }
         }
+    };
+
+    const int n_end = min(T, m0 + BM);
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    int buf = 0;
+    for (int n0 = 0; n0 < n_end; n0 += kFwdBN, buf ^= 1) {
+        const bool more = n0 + kFwdBN < n_end;
+        if (more) fetch(n0 + kFwdBN);
+
+        if (n0 <= mw + 31) {  // otherwise every key of the tile is in this wave's future
+            // S^T = K . Q^T : two 32-key blocks x this wave's 32 queries
+            f32x16 s[2];
+            {
+                bf16x8 ka[2][KB];  // every A fragment of the tile is requested before the first MFMA
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+                        ka[nb][kb] = *reinterpret_cast<const bf16x8*>(
+                            &ks[buf][(nb * 32 + c32) * KP + kb * 16 + h * 8]);
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+                        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[nb][kb], qf[kb], s[nb], 0, 0, 0);
+                // LDS reads run ahead of the matrix pipe: 4 in flight, then one read per MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+                for (int i = 0; i < 2 * KB - 4; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+            }
+            // causal mask (diagonal tiles only), row max on the raw products
+            if ((n0 + kFwdBN - 1 > mw) || (n0 + kFwdBN > T)) {
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int n = n0 + nb * 32 + (r / 4) * 8 + h * 4 + (r % 4);
+                        if (n > m || n >= T) s[nb][r] = -INFINITY;
+                    }
+            }
+            float mx = -INFINITY;
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[nb][r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * scale_log2e;
+            const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every query
+            const bool grew = m_new > m_run;
+            const float corr = exp2f(m_run - m_new);
+            m_run = m_new;
+            float psum = 0.f;
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(s[nb][r], scale_log2e, -m_new));
+                    s[nb][r] = p;
+                    psum += p;
+                }
+            l_run = l_run * corr + psum;
+
+            if (want_out) {
+                if (__any(grew)) {  // wave-uniform: the running max settles after a few tiles
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) o[db][r] *= corr;
+                }
+                // O^T += V^T . P^T, 16 keys per MFMA; slot s of half h <-> key 8g + 4h + s (g = g0, g0+1)
+                bf16x8 va[4][DB];
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const int nb = kk / 2, g0 = (kk % 2) * 2;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const uint16_t* row = &vs[buf][(db * 32 + c32) * kVtPitch + nb * 32 + h * 4];
+                        const uint2 lo = *reinterpret_cast<const uint2*>(row + g0 * 8);
+                        const uint2 hi = *reinterpret_cast<const uint2*>(row + (g0 + 1) * 8);
+                        va[kk][db] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+                    }
+                }
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const int nb = kk / 2, g0 = (kk % 2) * 2;
+                    bf16x8 pf;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        pf[t] = (__bf16)s[nb][g0 * 4 + t];
+                        pf[4 + t] = (__bf16)s[nb][(g0 + 1) * 4 + t];
+                    }
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[kk][db], pf, o[db], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x100, 4, 1);
+#pragma unroll
+                for (int i = 0; i < 4 * DB - 4; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
+            }
+        }
+        if (more) stage(buf ^ 1);  // that buffer was last read before the previous barrier
+        __syncthreads();
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
@@ -214,8 +284,8 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
 {
     constexpr int KB = D / 16;
     constexpr int QP = D + 8;
-    __shared__ __align__(16) uint16_t qs[kColBM * QP];
-    __shared__ __align__(16) float lse2[kColBM];  // row log-sum-exp in base-2 units
+    __shared__ __align__(16) uint16_t qs[2][kColBM * QP];
+    __shared__ __align__(16) float lse2[2][kColBM];  // row log-sum-exp in base-2 units
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int c32 = lane % 32, h = lane / 32;
@@ -234,41 +304,84 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
         kf[kb] = __builtin_bit_cast(bf16x8, x);
     }
 
-    float col = 0.f;
-    for (int m0 = (n0 / kColBM) * kColBM; m0 < T; m0 += kColBM) {
-        __syncthreads();
-        for (int c = tid; c < kColBM * (D / 8); c += kMfmaThreads) {
+    constexpr int QCH = kColBM * (D / 8) / kMfmaThreads;  // 16-byte chunks of the Q tile per thread
+    uint4 qreg[QCH];
+    float lreg = 0.f;
+    auto fetch = [&](int m0) {
+#pragma unroll
+        for (int i = 0; i < QCH; ++i) {
+            const int c = tid + i * kMfmaThreads;
             const int r = c / (D / 8), cc = c % (D / 8);
-            uint4 x = make_uint4(0, 0, 0, 0);
-            if (m0 + r < T) x = *reinterpret_cast<const uint4*>(qh + (size_t)(m0 + r) * D + cc * 8);
-            *reinterpret_cast<uint4*>(&qs[r * QP + cc * 8]) = x;
+            qreg[i] = make_uint4(0, 0, 0, 0);
+            if (m0 + r < T) qreg[i] = *reinterpret_cast<const uint4*>(qh + (size_t)(m0 + r) * D + cc * 8);
         }
-        if (tid < kColBM) lse2[tid] = (m0 + tid < T) ? lh[m0 + tid] * kLog2e : INFINITY;
-        __syncthreads();
-        if (m0 + kColBM - 1 < n0 + wave * 32) continue;  // every query of the tile precedes this wave's keys
+        if (tid < kColBM) lreg = (m0 + tid < T) ? lh[m0 + tid] * kLog2e : INFINITY;
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < QCH; ++i) {
+            const int c = tid + i * kMfmaThreads;
+            const int r = c / (D / 8), cc = c % (D / 8);
+            *reinterpret_cast<uint4*>(&qs[buf][r * QP + cc * 8]) = qreg[i];
+        }
+        if (tid < kColBM) lse2[buf][tid] = lreg;
+    };
 
+    float col = 0.f;
+    const int m_begin = (n0 / kColBM) * kColBM;
+    fetch(m_begin);
+    stage(0);
+    __syncthreads();
+    int buf = 0;
+    for (int m0 = m_begin; m0 < T; m0 += kColBM, buf ^= 1) {
+        const bool more = m0 + kColBM < T;
+        if (more) fetch(m0 + kColBM);
+
+        if (m0 + kColBM - 1 >= n0 + wave * 32) {  // else every query of the tile precedes this wave's keys
+            f32x16 s[2];
+            bf16x8 qa[2][KB];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            f32x16 s;
+            for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = 0.f;
+                for (int mb = 0; mb < 2; ++mb)
+                    qa[mb][kb] = *reinterpret_cast<const bf16x8*>(&qs[buf][(mb * 32 + c32) * QP + kb * 16 + h * 8]);
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&qs[(mb * 32 + c32) * QP + kb * 16 + h * 8]);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[kb], s, 0, 0, 0);
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[mb][r] = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+                    s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[mb][kb], kf[kb], s[mb], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+            for (int i = 0; i < 2 * KB - 4; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+
+            const bool diag = m0 < n0 + wave * 32 + 31;  // some (query, key) pair of the tile has query < key
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const float4 l4 = *reinterpret_cast<const float4*>(&lse2[mb * 32 + g * 8 + h * 4]);
-                const float lr[4] = {l4.x, l4.y, l4.z, l4.w};
+            for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int mm = m0 + mb * 32 + g * 8 + h * 4 + t;
-                    const float p = __builtin_amdgcn_exp2f(s[g * 4 + t] * scale_log2e - lr[t]);
-                    col += (mm >= n) ? p : 0.f;  // rows beyond T carry lse = +inf, so p = 0
+                for (int g = 0; g < 4; ++g) {
+                    const float4 l4 = *reinterpret_cast<const float4*>(&lse2[buf][mb * 32 + g * 8 + h * 4]);
+                    const float lr[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        float p = __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + t], scale_log2e, -lr[t]));
+                        if (diag) {
+                            const int mm = m0 + mb * 32 + g * 8 + h * 4 + t;
+                            p = (mm >= n) ? p : 0.f;
+                        }
+                        col += p;  // rows beyond T carry lse = +inf, so p = 0
+                    }
                 }
-            }
         }
+        if (more) stage(buf ^ 1);
+        __syncthreads();
     }
     col += __shfl_xor(col, 32, kWave);
     if (h == 0 && n < T) head_imp[(size_t)bh * T + n] = col;
@@ -276,7 +389,8 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
 
 template <int D>
 static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse,
-                       float* head_imp, uint16_t* vt, int B, int H, int T, float scale, hipStream_t stream)
+                       float* head_imp, uint16_t* vt, int B, int H, int T, float scale, int forced_waves,
+                       hipStream_t stream)
 {
     const float sl = scale * kLog2e;
     const int Tp = padded_T(T);
@@ -286,8 +400,16 @@ static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, 
         int rc = status_from_hip(hipGetLastError());
         if (rc != EC_OK) return rc;
     }
-    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D>), dim3((T + kFwdBM - 1) / kFwdBM, BH), dim3(kMfmaThreads), 0,
-                       stream, q, k, vt, out, lse, T, Tp, sl);
+    // 8-wave workgroups (256 queries) halve the LDS staging per flop; 4-wave ones keep small prompts
+    // spread over the chip
+    int waves = forced_waves;
+    if (waves != 4 && waves != 8) waves = ((long long)BH * ((T + 255) / 256) >= 512) ? 8 : 4;
+    if (waves == 8)
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 8>), dim3((T + 255) / 256, BH), dim3(512), 0, stream, q, k,
+                           vt, out, lse, T, Tp, sl);
+    else
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 4>), dim3((T + 127) / 128, BH), dim3(256), 0, stream, q, k,
+                           vt, out, lse, T, Tp, sl);
     int rc = status_from_hip(hipGetLastError());
     if (rc != EC_OK) return rc;
     hipLaunchKernelGGL((colsum_mfma_kernel<D>), dim3((T + kColBN - 1) / kColBN, BH), dim3(kMfmaThreads), 0,
@@ -300,15 +422,16 @@ size_t score_mfma_vt_bytes(int B, int H, int T, int D) { return (size_t)B * H * 
 
 // Per-head importance into head_imp [B,H,T]; out may be NULL (then vt is not touched).
 int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse, float* head_imp,
-                        void* vt, int B, int H, int T, int D, int dt, float scale, hipStream_t stream)
+                        void* vt, int B, int H, int T, int D, int dt, float scale, int forced_waves,
+                        hipStream_t stream)
 {
     if (dt != EC_BF16) return EC_EUNSUPPORTED;
     if (D == 128)
         return launch_mfma<128>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out, lse,
-                                head_imp, (uint16_t*)vt, B, H, T, scale, stream);
+                                head_imp, (uint16_t*)vt, B, H, T, scale, forced_waves, stream);
     if (D == 64)
         return launch_mfma<64>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out, lse,
-                               head_imp, (uint16_t*)vt, B, H, T, scale, stream);
+                               head_imp, (uint16_t*)vt, B, H, T, scale, forced_waves, stream);
     return EC_EUNSUPPORTED;
 }
 

@@ -233,21 +233,29 @@ __global__ __launch_bounds__(kSimtThreads) void colsum_simt_kernel(
 }
 
 // score[b][n] = (1/H) sum_h head_imp[b][h][n], heads added in ascending order.
-__global__ __launch_bounds__(256) void head_mean_kernel(const float* __restrict__ head_imp,
+__global__ __launch_bounds__(64) void head_mean_kernel(const float* __restrict__ head_imp,
                                                         float* __restrict__ score, int H, int T)
 {
     const int b = blockIdx.y;
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= T) return;
+    // loads are issued 8 at a time; the additions keep ascending head order
     float acc = 0.f;
-    for (int h = 0; h < H; ++h) acc += head_imp[((size_t)b * H + h) * T + n];
+    int h = 0;
+    for (; h + 8 <= H; h += 8) {
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = head_imp[((size_t)b * H + h + j) * T + n];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc += x[j];
+    }
+    for (; h < H; ++h) acc += head_imp[((size_t)b * H + h) * T + n];
     score[(size_t)b * T + n] = acc / (float)H;
 }
 
 int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, hipStream_t stream)
 {
-    hipLaunchKernelGGL(head_mean_kernel, dim3((T + 255) / 256, B), dim3(256), 0, stream, head_imp, score,
-                       H, T);
+    hipLaunchKernelGGL(head_mean_kernel, dim3((T + 63) / 64, B), dim3(64), 0, stream, head_imp, score, H, T);
     return status_from_hip(hipGetLastError());
 }
 
