@@ -35,6 +35,10 @@ def parse():
     ap.add_argument("--score-mode", default="layer", choices=["layer", "head"])
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-steps", type=int, default=0,
+                    help="profiling aid: run only the first N generated tokens (the JSON line says so)")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also launch one plain device copy of this many MiB (reference dispatch for HBM counters)")
     ap.add_argument("--distinct-layers", type=int, default=0,
                     help="distinct prompt tensors to generate (0 = one per layer; fewer are cycled)")
     return ap.parse_args()
@@ -171,47 +175,56 @@ def timed(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-def cpu_baseline(cfg, wl, G):
-    """Time the fp64 oracle on a bounded sample of the same workload and scale to whole-job tokens/s."""
+def cpu_baseline(cfg, wl, G, budget_s=20.0):
+    """Time the fp64 oracle (as it stands) on a bounded sample of the same workload, scaled to whole-job tokens/s."""
     import numpy as np
     import oracle
-    torch = wl.torch
     B, H, T, D, L = cfg.B, cfg.H, cfg.T, cfg.D, cfg.layers
-    # prefill sample: layer 0, as many batch elements as keep the fp64 brute force near 10-20 s
-    flops_per_b = 2.0 * 2.0 * D * T * (T + 1) / 2 * H
-    nb = max(1, min(B, int(6e10 // flops_per_b)))
-    heads = H
-    if flops_per_b > 1.2e11:   # even one batch element is too long: time a subset of heads (G=H semantics)
-        heads = max(1, int(H * 1.2e11 // flops_per_b))
-    q, k, v = (x[:nb, :heads].float().cpu().numpy() for x in wl.prompts[0])
-    t0 = time.perf_counter()
-    r = oracle.prefill_score(q, k, v, cfg.scale, 1 if heads == H and G == 1 else heads, want_out=True)
-    t_score = time.perf_counter() - t0
-    sc32 = r["score"].astype(np.float32)
-    t0 = time.perf_counter()
-    a = oracle.select_anchors(sc32, cfg.n_anchor, 1, 1)
-    assign, _ = oracle.assign_nearest(a, T)
-    kc = oracle.merge_compact(k, assign, cfg.n_anchor, cfg.cap)
-    vc = oracle.merge_compact(v, assign, cfg.n_anchor, cfg.cap)
-    t_rest = time.perf_counter() - t0
-    frac = (nb * heads) / (B * H)
-    t_prefill_layer = (t_score + t_rest) / frac
-    # decode sample: a few steps of layer 0 at the first, middle and last cache length
-    lens = sorted({cfg.n_anchor, (cfg.n_anchor + wl.final_len) // 2, wl.final_len - 1})
-    dq, dk, dv = (x[:3, :nb, :heads].float().cpu().numpy() for x in wl.dec[0])
-    t_dec = []
-    for i, n in enumerate(lens):
-        n = min(n, cfg.cap - 1)
+    # one layer of the fp64 brute force costs ~4*D*T^2/2*B*H flop; bound one sample layer to ~6e11 flop
+    flops_per_b = 2.0 * D * T * (T + 1) * H
+    nb = max(1, min(B, int(6e11 // flops_per_b)))
+    frac = nb / B
+    t_start = time.perf_counter()
+    t_prefill, n_layers = [], 0
+    kc = vc = None
+    for l in range(L):
+        q, k, v = (x[:nb].float().cpu().numpy() for x in wl.prompts[l % len(wl.prompts)])
         t0 = time.perf_counter()
-        oracle.decode_step(dq[i % 3], dk[i % 3], dv[i % 3], kc, vc, None, n, max(1, n - 25), 0, cfg.scale)
-        t_dec.append(time.perf_counter() - t0)
+        r = oracle.prefill_score(q, k, v, cfg.scale, G, want_out=True)
+        a = oracle.select_anchors(r["score"].astype(np.float32), cfg.n_anchor, 1, 1)
+        assign, _ = oracle.assign_nearest(a, T)
+        kc = oracle.merge_compact(k, assign, cfg.n_anchor, cfg.cap)
+        vc = oracle.merge_compact(v, assign, cfg.n_anchor, cfg.cap)
+        t_prefill.append(time.perf_counter() - t0)
+        n_layers += 1
+        if time.perf_counter() - t_start > 0.6 * budget_s:
+            break
+    # decode: steps spread over the run, each at the cache length the schedule has there
+    p, qd = cfg.gamma
+    lens, N = [], cfg.n_anchor
+    for step in range(cfg.decode_steps):
+        idx = oracle.evict_index(T + step + 1, N + 1, p, qd)
+        lens.append((N, idx))
+        N += 0 if idx >= 0 else 1
+    t_dec, n_dec_layers = [], 0
+    for l in range(L):          # whole decode runs of successive layers until the budget is used
+        dq, dk, dv = (x[:, :nb].float().cpu().numpy() for x in wl.dec[l])
+        for step in range(cfg.decode_steps):
+            n, idx = lens[step]
+            t0 = time.perf_counter()
+            oracle.decode_step(dq[step], dk[step], dv[step], kc, vc, None, n, idx, T + step, cfg.scale)
+            t_dec.append(time.perf_counter() - t0)
+        n_dec_layers += 1
+        if time.perf_counter() - t_start > budget_s:
+            break
+    t_prefill_layer = float(np.mean(t_prefill)) / frac
     t_decode_layer_step = float(np.mean(t_dec)) / frac
     total = L * t_prefill_layer + L * cfg.decode_steps * t_decode_layer_step
     return {
         "value": B * cfg.decode_steps / total, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-        "sample": (f"layer 0, {nb}/{B} batch elements x {heads}/{H} heads: score+select+merge {t_score + t_rest:.2f} s, "
-                   f"{len(lens)} decode steps at cache lengths {lens} {sum(t_dec):.3f} s; scaled linearly to "
-                   f"{L} layers x {cfg.decode_steps} steps x full batch"),
+        "sample": (f"{nb}/{B} batch elements, all {H} heads: score+select+merge of {n_layers} layer(s) "
+                   f"{sum(t_prefill):.2f} s, all {cfg.decode_steps} decode steps of {n_dec_layers} layer(s) {sum(t_dec):.2f} s; "
+                   f"scaled linearly to {L} layers x {cfg.decode_steps} steps x full batch"),
         "prefill_s_per_layer": t_prefill_layer, "decode_s_per_layer_step": t_decode_layer_step,
     }
 
@@ -228,10 +241,21 @@ def main():
         print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     cfg = syn.CONFIGS[args.config]
+    truncated = 0 < args.decode_steps < cfg.decode_steps
+    if truncated:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, decode_steps=args.decode_steps)
     wl = Workload(cfg, args.score_mode, args.distinct_layers)
     L, B = cfg.layers, cfg.B
     torch.cuda.synchronize()
+    if args.calib_copy_mb > 0:  # a copy of known size, so that profiler byte counters can be scaled
+        src = torch.empty(args.calib_copy_mb << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
+    print(f"[bench] workload {cfg.name} resident; eager pass", file=sys.stderr, flush=True)
     eager_prefill = lambda: wl.run_prefill(wl._stream())
     eager_decode = lambda: wl.run_decode(wl._stream())
     # eager pass first: also validates every argument before anything is captured
@@ -246,6 +270,7 @@ def main():
     do_prefill = replay_prefill if use_graph else eager_prefill
     do_decode = replay_decode if use_graph else eager_decode
 
+    print(f"[bench] launch mode {'hipgraph' if use_graph else 'eager'}; warmup + timed steps", file=sys.stderr, flush=True)
     for _ in range(args.warmup):
         do_prefill()
         do_decode()
@@ -266,11 +291,15 @@ def main():
     decode_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
     ms_per_step = max(wall_ms, prefill_ms + decode_ms)
 
-    # ---- per-call breakdown (outside the timed region above, same buffers) ----
-    reps = 3
-    score_ms = timed(torch, lambda: wl.run_score(wl._stream()), reps) / L
-    select_ms = timed(torch, lambda: wl.run_select(wl._stream()), reps) / L
-    merge_ms = timed(torch, lambda: wl.run_merge(wl._stream()), reps) / L
+    print("[bench] timed region done; per-call breakdown", file=sys.stderr, flush=True)
+    # ---- per-call breakdown (outside the timed region above, same buffers, same launch mode) ----
+    def per_layer_ms(run):
+        fn = (capture(torch, run) if use_graph else None) or (lambda: run(wl._stream()))
+        fn()
+        return timed(torch, fn, 3) / L
+    score_ms = per_layer_ms(wl.run_score)
+    select_ms = per_layer_ms(wl.run_select)
+    merge_ms = per_layer_ms(wl.run_merge)
     do_prefill()  # restore the compressed caches for whoever looks at them next
     torch.cuda.synchronize()
 
@@ -290,7 +319,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {L} layers, {cfg.H} heads, head_dim {cfg.D}, batch {B}, prompt {cfg.T}, "
                                f"budget {cfg.gamma[0]}/{cfg.gamma[1]}, {cfg.decode_steps} decode steps, {cfg.dtype}",
-                   "score_mode": args.score_mode, "launch": "hipgraph" if use_graph else "eager",
+                   "score_mode": args.score_mode, "launch": "hipgraph" if use_graph else "eager", "truncated_decode": truncated,
                    "cache_len": [cfg.n_anchor, wl.final_len]},
         "detail": {
             "decode_attn_GBps": dec_gbps, "decode_tokens_per_s": B * cfg.decode_steps / (decode_ms * 1e-3),
@@ -314,6 +343,7 @@ def main():
         },
     }
     if not args.no_cpu_baseline:
+        print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         res["cpu_baseline"] = cpu_baseline(cfg, wl, wl.G)
     print(json.dumps(res))
 

@@ -36,6 +36,18 @@ constexpr int kVtPitch = kFwdBN + 4;  // bf16 elements per V^T row in LDS (136 B
 
 __host__ __device__ inline int padded_T(int T) { return (T + 63) / 64 * 64; }
 
+// Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  Work
+// items are therefore renumbered so that one XCD gets a CONTIGUOUS range of items: all tiles of a
+// head (which share its K and V) then sit behind the same L2 instead of being fetched eight times.
+constexpr int kXcds = 8;
+inline int xcd_grid(int total) { return (total + kXcds - 1) / kXcds * kXcds; }
+__device__ __forceinline__ int xcd_contiguous_item(int linear_id, int total)
+{
+    const int per_xcd = (total + kXcds - 1) / kXcds;
+    if (linear_id / kXcds >= per_xcd) return total;
+    return (linear_id % kXcds) * per_xcd + linear_id / kXcds;  // may be >= total: caller exits
+}
+
 // ------------------------------------------------------------------ V^T
 __global__ __launch_bounds__(256) void vt_transpose_kernel(const uint16_t* __restrict__ v,
                                                            uint16_t* __restrict__ vt, int T, int Tp, int D)
@@ -67,7 +79,8 @@ __global__ __launch_bounds__(256) void vt_transpose_kernel(const uint16_t* __res
 template <int D, int WAVES>
 __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
-    uint16_t* __restrict__ out, float* __restrict__ lse, int T, int Tp, float scale_log2e)
+    uint16_t* __restrict__ out, float* __restrict__ lse, int T, int Tp, float scale_log2e, int n_qtiles,
+    int n_heads)
 {
     constexpr int THREADS = WAVES * kWave;
     constexpr int BM = WAVES * 32;   // queries per workgroup
@@ -81,9 +94,11 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int c32 = lane % 32, h = lane / 32;
-    const int bh = blockIdx.y;
-    const int m0 = (gridDim.x - 1 - blockIdx.x) * BM;  // longest rows first
-    const int mw = m0 + wave * 32;                     // first query of this wave
+    const int item = xcd_contiguous_item(blockIdx.x, n_qtiles * n_heads);
+    if (item >= n_qtiles * n_heads) return;
+    const int bh = item / n_qtiles;
+    const int m0 = (n_qtiles - 1 - item % n_qtiles) * BM;  // longest rows first inside a head
+    const int mw = m0 + wave * 32;                          // first query of this wave
     const int m = mw + c32;                            // this lane's query
     const uint16_t* qh = q + (size_t)bh * T * D;
     const uint16_t* kh = k + (size_t)bh * T * D;
@@ -280,7 +295,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 template <int D>
 __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const float* __restrict__ lse,
-    float* __restrict__ head_imp, int T, float scale_log2e)
+    float* __restrict__ head_imp, int T, float scale_log2e, int n_ktiles, int n_heads)
 {
     constexpr int KB = D / 16;
     constexpr int QP = D + 8;
@@ -289,8 +304,10 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int c32 = lane % 32, h = lane / 32;
-    const int bh = blockIdx.y;
-    const int n0 = blockIdx.x * kColBN;  // low key tiles (most query tiles) are scheduled first
+    const int item = xcd_contiguous_item(blockIdx.x, n_ktiles * n_heads);
+    if (item >= n_ktiles * n_heads) return;
+    const int bh = item / n_ktiles;
+    const int n0 = (item % n_ktiles) * kColBN;  // low key tiles (most query tiles) first inside a head
     const int n = n0 + wave * 32 + c32;  // this lane's key
     const uint16_t* qh = q + (size_t)bh * T * D;
     const uint16_t* kh = k + (size_t)bh * T * D;
@@ -405,15 +422,15 @@ static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, 
     int waves = forced_waves;
     if (waves != 4 && waves != 8) waves = ((long long)BH * ((T + 255) / 256) >= 512) ? 8 : 4;
     if (waves == 8)
-        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 8>), dim3((T + 255) / 256, BH), dim3(512), 0, stream, q, k,
-                           vt, out, lse, T, Tp, sl);
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 8>), dim3(xcd_grid(((T + 255) / 256) * BH)), dim3(512), 0,
+                           stream, q, k, vt, out, lse, T, Tp, sl, (T + 255) / 256, BH);
     else
-        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 4>), dim3((T + 127) / 128, BH), dim3(256), 0, stream, q, k,
-                           vt, out, lse, T, Tp, sl);
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 4>), dim3(xcd_grid(((T + 127) / 128) * BH)), dim3(256), 0,
+                           stream, q, k, vt, out, lse, T, Tp, sl, (T + 127) / 128, BH);
     int rc = status_from_hip(hipGetLastError());
     if (rc != EC_OK) return rc;
-    hipLaunchKernelGGL((colsum_mfma_kernel<D>), dim3((T + kColBN - 1) / kColBN, BH), dim3(kMfmaThreads), 0,
-                       stream, q, k, lse, head_imp, T, sl);
+    hipLaunchKernelGGL((colsum_mfma_kernel<D>), dim3(xcd_grid(((T + kColBN - 1) / kColBN) * BH)),
+                       dim3(kMfmaThreads), 0, stream, q, k, lse, head_imp, T, sl, (T + kColBN - 1) / kColBN, BH);
     return status_from_hip(hipGetLastError());
 }
 
