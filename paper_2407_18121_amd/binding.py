@@ -12,7 +12,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libelastic_cache.so")
+LIB_PATH = os.environ.get("EC_LIB_PATH", os.path.join(_HERE, "libelastic_cache.so"))
 
 EC_OK, EC_EINVAL, EC_EUNSUPPORTED, EC_EWORKSPACE, EC_EDEVICE = range(5)
 EC_F32, EC_BF16 = 0, 1

@@ -22,17 +22,22 @@
 //   C (32 x 32): lane holds C[8g + 4h + t][l % 32] in register 4g + t, g,t in 0..3
 #include "ec_common.h"
 
+#ifndef EC_COLSUM_VARIANT
+#define EC_COLSUM_VARIANT 0
+#endif
+
 namespace ec {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // 16-byte staging register (native vector: stays in VGPRs)
 
 constexpr int kMfmaThreads = 256;
 constexpr int kFwdBN = 64;   // keys per LDS tile
 constexpr int kColBN = 128;  // keys per workgroup in colsum (32 per wave)
 constexpr int kColBM = 64;   // queries per LDS tile in colsum
-constexpr int kVtPitch = kFwdBN + 4;  // bf16 elements per V^T row in LDS (136 B: conflict-free b64 reads)
+constexpr int kVtPitch = kFwdBN + 8;  // bf16 elements per V^T row in LDS (144 B: conflict-free b128 reads)
 
 __host__ __device__ inline int padded_T(int T) { return (T + 63) / 64 * 64; }
 
@@ -94,6 +99,11 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int c32 = lane % 32, h = lane / 32;
+    // LDS row j of the K tile holds key swap23(j) (bits 2 and 3 of the row number exchanged), i.e. row
+    // i of a 32-key S^T block is key 16(i/16) + 8((i/4)%2) + 4((i/8)%2) + i%4.  In the accumulator
+    // layout (register 4g+t of half h = row 8g+4h+t) registers 8G..8G+7 of a lane then hold the 8
+    // CONSECUTIVE keys 16G + 8h .. +7: the P fragment of a P.V MFMA is a run of registers and its V^T
+    // operand a single 16-byte LDS read, while the K-tile reads stay linear and conflict-free.
     const int item = xcd_contiguous_item(blockIdx.x, n_qtiles * n_heads);
     if (item >= n_qtiles * n_heads) return;
     const int bh = item / n_qtiles;
@@ -120,21 +130,21 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
         for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;  // l_run: this half-wave's share of the row sum
 
-    uint4 kreg[KCH], vreg[VCH];
+    u32x4 kreg[KCH], vreg[VCH];
     auto fetch = [&](int n0) {
 #pragma unroll
         for (int i = 0; i < KCH; ++i) {
             const int c = tid + i * THREADS;
             const int r = c / (D / 8), cc = c % (D / 8);
-            kreg[i] = make_uint4(0, 0, 0, 0);
-            if (n0 + r < T) kreg[i] = *reinterpret_cast<const uint4*>(kh + (size_t)(n0 + r) * D + cc * 8);
+            kreg[i] = u32x4{0u, 0u, 0u, 0u};
+            if (n0 + r < T) kreg[i] = *reinterpret_cast<const u32x4*>(kh + (size_t)(n0 + r) * D + cc * 8);
         }
         if (want_out) {
 #pragma unroll
             for (int i = 0; i < VCH; ++i) {
                 const int c = tid + i * THREADS;
                 const int d = c / (kFwdBN / 8), cc = c % (kFwdBN / 8);
-                vreg[i] = *reinterpret_cast<const uint4*>(vth + (size_t)d * Tp + n0 + cc * 8);
+                vreg[i] = *reinterpret_cast<const u32x4*>(vth + (size_t)d * Tp + n0 + cc * 8);
             }
         }
     };
@@ -143,16 +153,15 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
         for (int i = 0; i < KCH; ++i) {
             const int c = tid + i * THREADS;
             const int r = c / (D / 8), cc = c % (D / 8);
-            *reinterpret_cast<uint4*>(&ks[buf][r * KP + cc * 8]) = kreg[i];
+            const int lr = (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);  // swap23
+            *reinterpret_cast<u32x4*>(&ks[buf][lr * KP + cc * 8]) = kreg[i];
         }
         if (want_out) {
 #pragma unroll
             for (int i = 0; i < VCH; ++i) {
                 const int c = tid + i * THREADS;
                 const int d = c / (kFwdBN / 8), cc = c % (kFwdBN / 8);
-                uint2* dst = reinterpret_cast<uint2*>(&vs[buf][d * kVtPitch + cc * 8]);
-                dst[0] = make_uint2(vreg[i].x, vreg[i].y);
-                dst[1] = make_uint2(vreg[i].z, vreg[i].w);
+                *reinterpret_cast<u32x4*>(&vs[buf][d * kVtPitch + cc * 8]) = vreg[i];
             }
         }
     };
@@ -201,7 +210,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
                 for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int n = n0 + nb * 32 + (r / 4) * 8 + h * 4 + (r % 4);
+                        const int n = n0 + nb * 32 + (r / 8) * 16 + h * 8 + (r % 8);  // key of register r
                         if (n > m || n >= T) s[nb][r] = -INFINITY;
                     }
             }
@@ -233,28 +242,20 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 #pragma unroll
                         for (int r = 0; r < 16; ++r) o[db][r] *= corr;
                 }
-                // O^T += V^T . P^T, 16 keys per MFMA; slot s of half h <-> key 8g + 4h + s (g = g0, g0+1)
+                // O^T += V^T . P^T, 16 keys per MFMA: half h contracts keys 16G + 8h .. +7 (G = kk % 2)
                 bf16x8 va[4][DB];
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    const int nb = kk / 2, g0 = (kk % 2) * 2;
+                for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-                    for (int db = 0; db < DB; ++db) {
-                        const uint16_t* row = &vs[buf][(db * 32 + c32) * kVtPitch + nb * 32 + h * 4];
-                        const uint2 lo = *reinterpret_cast<const uint2*>(row + g0 * 8);
-                        const uint2 hi = *reinterpret_cast<const uint2*>(row + (g0 + 1) * 8);
-                        va[kk][db] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-                    }
-                }
+                    for (int db = 0; db < DB; ++db)
+                        va[kk][db] = *reinterpret_cast<const bf16x8*>(
+                            &vs[buf][(db * 32 + c32) * kVtPitch + kk * 16 + h * 8]);
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
-                    const int nb = kk / 2, g0 = (kk % 2) * 2;
+                    const int nb = kk / 2, r0 = (kk % 2) * 8;
                     bf16x8 pf;
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        pf[t] = (__bf16)s[nb][g0 * 4 + t];
-                        pf[4 + t] = (__bf16)s[nb][(g0 + 1) * 4 + t];
-                    }
+                    for (int t = 0; t < 8; ++t) pf[t] = (__bf16)s[nb][r0 + t];
 #pragma unroll
                     for (int db = 0; db < DB; ++db)
                         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[kk][db], pf, o[db], 0, 0, 0);
@@ -322,15 +323,15 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
     }
 
     constexpr int QCH = kColBM * (D / 8) / kMfmaThreads;  // 16-byte chunks of the Q tile per thread
-    uint4 qreg[QCH];
+    u32x4 qreg[QCH];
     float lreg = 0.f;
     auto fetch = [&](int m0) {
 #pragma unroll
         for (int i = 0; i < QCH; ++i) {
             const int c = tid + i * kMfmaThreads;
             const int r = c / (D / 8), cc = c % (D / 8);
-            qreg[i] = make_uint4(0, 0, 0, 0);
-            if (m0 + r < T) qreg[i] = *reinterpret_cast<const uint4*>(qh + (size_t)(m0 + r) * D + cc * 8);
+            qreg[i] = u32x4{0u, 0u, 0u, 0u};
+            if (m0 + r < T) qreg[i] = *reinterpret_cast<const u32x4*>(qh + (size_t)(m0 + r) * D + cc * 8);
         }
         if (tid < kColBM) lreg = (m0 + tid < T) ? lh[m0 + tid] * kLog2e : INFINITY;
     };
@@ -339,7 +340,7 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
         for (int i = 0; i < QCH; ++i) {
             const int c = tid + i * kMfmaThreads;
             const int r = c / (D / 8), cc = c % (D / 8);
-            *reinterpret_cast<uint4*>(&qs[buf][r * QP + cc * 8]) = qreg[i];
+            *reinterpret_cast<u32x4*>(&qs[buf][r * QP + cc * 8]) = qreg[i];
         }
         if (tid < kColBM) lse2[buf][tid] = lreg;
     };
@@ -370,7 +371,11 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
             for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)
+#if EC_COLSUM_VARIANT == 3
+                    s[mb][kb] += __builtin_bit_cast(float4, qa[mb][kb]).x * __builtin_bit_cast(float4, kf[kb]).y;
+#else
                     s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[mb][kb], kf[kb], s[mb], 0, 0, 0);
+#endif
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
             for (int i = 0; i < 2 * KB - 4; ++i) {
@@ -388,7 +393,13 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
                     const float lr[4] = {l4.x, l4.y, l4.z, l4.w};
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
+#if EC_COLSUM_VARIANT == 1
+                        float p = fmaf(s[mb][g * 4 + t], scale_log2e, -lr[t]);
+#elif EC_COLSUM_VARIANT == 2
+                        float p = (t == 0 && g == 0) ? s[mb][0] + lr[0] : 0.f;
+#else
                         float p = __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + t], scale_log2e, -lr[t]));
+#endif
                         if (diag) {
                             const int mm = m0 + mb * 32 + g * 8 + h * 4 + t;
                             p = (mm >= n) ? p : 0.f;
