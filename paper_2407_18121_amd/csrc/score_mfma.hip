@@ -22,10 +22,6 @@
 //   C (32 x 32): lane holds C[8g + 4h + t][l % 32] in register 4g + t, g,t in 0..3
 #include "ec_common.h"
 
-#ifndef EC_COLSUM_VARIANT
-#define EC_COLSUM_VARIANT 0
-#endif
-
 namespace ec {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -371,11 +367,7 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
             for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)
-#if EC_COLSUM_VARIANT == 3
-                    s[mb][kb] += __builtin_bit_cast(float4, qa[mb][kb]).x * __builtin_bit_cast(float4, kf[kb]).y;
-#else
                     s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[mb][kb], kf[kb], s[mb], 0, 0, 0);
-#endif
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
             for (int i = 0; i < 2 * KB - 4; ++i) {
@@ -384,29 +376,37 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
 
+            // p = exp(s - lse_row), summed down the column.  Only tiles that touch the diagonal need
+            // the causal mask; the others take the three-instruction path (fma, exp, add).
             const bool diag = m0 < n0 + wave * 32 + 31;  // some (query, key) pair of the tile has query < key
+            if (diag) {
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+                for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 l4 = *reinterpret_cast<const float4*>(&lse2[buf][mb * 32 + g * 8 + h * 4]);
-                    const float lr[4] = {l4.x, l4.y, l4.z, l4.w};
+                    for (int g = 0; g < 4; ++g) {
+                        const float4 l4 = *reinterpret_cast<const float4*>(&lse2[buf][mb * 32 + g * 8 + h * 4]);
+                        const float lr[4] = {l4.x, l4.y, l4.z, l4.w};
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-#if EC_COLSUM_VARIANT == 1
-                        float p = fmaf(s[mb][g * 4 + t], scale_log2e, -lr[t]);
-#elif EC_COLSUM_VARIANT == 2
-                        float p = (t == 0 && g == 0) ? s[mb][0] + lr[0] : 0.f;
-#else
-                        float p = __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + t], scale_log2e, -lr[t]));
-#endif
-                        if (diag) {
+                        for (int t = 0; t < 4; ++t) {
+                            const float p = __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + t], scale_log2e, -lr[t]));
                             const int mm = m0 + mb * 32 + g * 8 + h * 4 + t;
-                            p = (mm >= n) ? p : 0.f;
+                            col += (mm >= n) ? p : 0.f;  // rows beyond T carry lse = +inf, so p = 0
                         }
-                        col += p;  // rows beyond T carry lse = +inf, so p = 0
                     }
-                }
+            } else {
+                float c0 = 0.f, c1 = 0.f;  // two chains keep the adds off the exp latency
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const float4 l4 = *reinterpret_cast<const float4*>(&lse2[buf][mb * 32 + g * 8 + h * 4]);
+                        c0 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 0], scale_log2e, -l4.x));
+                        c1 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 1], scale_log2e, -l4.y));
+                        c0 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 2], scale_log2e, -l4.z));
+                        c1 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 3], scale_log2e, -l4.w));
+                    }
+                col += c0 + c1;
+            }
         }
         if (more) stage(buf ^ 1);
         __syncthreads();
