@@ -13,7 +13,7 @@
 namespace ec {
 
 constexpr int kMergeThreads = 256;
-constexpr int kMergeUnroll = 4;
+constexpr int kMergeUnroll = 8;  // rows in flight per bucket: long buckets are latency chains otherwise
 
 // Inclusive bounds of bucket j for ascending anchors a[0..n).  Clamped so that a
 // malformed anchor list can never index outside [0,T).
@@ -30,7 +30,8 @@ __device__ __forceinline__ void bucket_bounds(const int32_t* __restrict__ a, int
 template <int DT, int D>
 __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     const uint4* __restrict__ k, const uint4* __restrict__ v, const int32_t* __restrict__ anchor_idx,
-    uint4* __restrict__ k_cache, uint4* __restrict__ v_cache, int H, int G, int T, int n_anchor, int cap)
+    uint4* __restrict__ k_cache, uint4* __restrict__ v_cache, int32_t* __restrict__ counts,
+    int32_t* __restrict__ assign, int32_t* __restrict__ pos, int H, int G, int T, int n_anchor, int cap)
 {
     constexpr int LPR = D * Elem<DT>::kBytes / 16;
     constexpr int EPL = Elem<DT>::kPerChunk;
@@ -52,24 +53,23 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
-    int t = lo;
-    for (; t + kMergeUnroll - 1 <= hi; t += kMergeUnroll) {
+    for (int t = lo; t <= hi; t += kMergeUnroll) {
         uint4 c[kMergeUnroll];
 #pragma unroll
-        for (int u = 0; u < kMergeUnroll; ++u) c[u] = src[(size_t)(t + u) * LPR];
+        for (int u = 0; u < kMergeUnroll; ++u) {
+            c[u] = make_uint4(0, 0, 0, 0);
+            if (t + u <= hi) c[u] = src[(size_t)(t + u) * LPR];
+        }
 #pragma unroll
         for (int u = 0; u < kMergeUnroll; ++u) {
-            float x[EPL];
-            unpack<DT>(c[u], x);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] += x[e];
+            if (t + u <= hi) {
+                float x[EPL];
+                unpack<DT>(c[u], x);
+                const bool first = (u == 0 && t == lo);  // the sum starts from the first row, so a bucket
+#pragma unroll                                           // of one is a bit-exact copy (-0 stays -0)
+                for (int e = 0; e < EPL; ++e) acc[e] = first ? x[e] : acc[e] + x[e];
+            }
         }
-    }
-    for (; t <= hi; ++t) {
-        float x[EPL];
-        unpack<DT>(src[(size_t)t * LPR], x);
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] += x[e];
     }
     const int count = hi - lo + 1;
     if (count > 1) {
@@ -78,38 +78,30 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
         for (int e = 0; e < EPL; ++e) acc[e] = acc[e] / cf;
     }
     *dst = pack<DT>(acc);
-}
 
-// Bookkeeping per score group: bucket sizes, bucket number of every position,
-// original position of every cache row.
-__global__ __launch_bounds__(256) void bucket_meta_kernel(const int32_t* __restrict__ anchor_idx,
-                                                          int T, int n_anchor, int cap,
-                                                          int32_t* __restrict__ counts,
-                                                          int32_t* __restrict__ assign,
-                                                          int32_t* __restrict__ pos)
-{
-    const int bg = blockIdx.y;
-    const int32_t* a = anchor_idx + (size_t)bg * n_anchor;
-    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < n_anchor; j += gridDim.x * blockDim.x) {
-        int lo, hi;
-        bucket_bounds(a, j, n_anchor, T, lo, hi);
-        if (counts) counts[(size_t)bg * n_anchor + j] = hi - lo + 1;
-        if (pos) pos[(size_t)bg * cap + j] = a[j];
+    // bookkeeping, once per score group: bucket size, position of the cache row, bucket of every position
+    if (blockIdx.z == 0 && (G == H || h == 0)) {
+        const size_t bg = (size_t)b * G + (G == 1 ? 0 : h);
+        if (sub == 0) {
+            if (counts) counts[bg * n_anchor + j] = count;
+            if (pos) pos[bg * cap + j] = a[j];
+        }
         if (assign)
-            for (int t = lo; t <= hi; ++t) assign[(size_t)bg * T + t] = j;
+            for (int t = lo + sub; t <= hi; t += LPR) assign[bg * T + t] = j;
     }
 }
 
 template <int DT, int D>
 static int launch_merge(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G,
-                        int T, int n_anchor, void* k_cache, void* v_cache, int cap, hipStream_t stream)
+                        int T, int n_anchor, void* k_cache, void* v_cache, int cap, int32_t* counts, int32_t* assign,
+                        int32_t* pos, hipStream_t stream)
 {
     constexpr int LPR = D * Elem<DT>::kBytes / 16;
     constexpr int GROUPS = kMergeThreads / LPR;
     dim3 grid((n_anchor + GROUPS - 1) / GROUPS, B * H, 2);
     hipLaunchKernelGGL((merge_compact_kernel<DT, D>), grid, dim3(kMergeThreads), 0, stream,
                        (const uint4*)k, (const uint4*)v, anchor_idx, (uint4*)k_cache, (uint4*)v_cache,
-                       H, G, T, n_anchor, cap);
+                       counts, assign, pos, H, G, T, n_anchor, cap);
     return status_from_hip(hipGetLastError());
 }
 
@@ -117,23 +109,16 @@ int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, int 
                    int D, int n_anchor, int dt, void* k_cache, void* v_cache, int cap, int32_t* counts,
                    int32_t* assign, int32_t* pos, hipStream_t stream)
 {
-    int rc = EC_EUNSUPPORTED;
 #define EC_MERGE_CASE(DT_, D_)                                                                      \
     if (dt == DT_ && D == D_)                                                                       \
-        rc = launch_merge<DT_, D_>(k, v, anchor_idx, B, H, G, T, n_anchor, k_cache, v_cache, cap, stream);
+        return launch_merge<DT_, D_>(k, v, anchor_idx, B, H, G, T, n_anchor, k_cache, v_cache, cap, counts, \
+                                     assign, pos, stream);
     EC_MERGE_CASE(EC_BF16, 128)
     EC_MERGE_CASE(EC_BF16, 64)
     EC_MERGE_CASE(EC_F32, 128)
     EC_MERGE_CASE(EC_F32, 64)
 #undef EC_MERGE_CASE
-    if (rc != EC_OK) return rc;
-    if (counts || assign || pos) {
-        dim3 grid((n_anchor + 255) / 256, B * G);
-        hipLaunchKernelGGL(bucket_meta_kernel, grid, dim3(256), 0, stream, anchor_idx, T, n_anchor, cap,
-                           counts, assign, pos);
-        rc = status_from_hip(hipGetLastError());
-    }
-    return rc;
+    return EC_EUNSUPPORTED;
 }
 
 }  // namespace ec
