@@ -24,6 +24,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 FP32_VALU_PEAK_TFLOPS = 157.3
+# HBM bytes actually moved per algorithmic byte, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/decode_step_C2_hbm_traffic.txt (counters scaled by a 256 MiB device copy in the same run)
+DECODE_TRAFFIC_RATIO = {"C2": 1.04}
 
 
 def parse():
@@ -333,7 +336,8 @@ def main():
         },
         "roofline": {
             "kernel": "decode_step_kernel", "bound": "hbm", "achieved": dec_gbps, "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s", "frac": dec_gbps / HBM_PEAK_GBPS, "traffic": None,
+            "unit": "GB/s", "frac": dec_gbps / HBM_PEAK_GBPS,
+            "traffic": (DECODE_TRAFFIC_RATIO[cfg.name] * wl.decode_bytes / n_dec) if cfg.name in DECODE_TRAFFIC_RATIO else None,
             "bytes_per_launch": wl.decode_bytes / n_dec, "us_per_launch": dec_launch_us,
         },
         "roofline_score": {

@@ -3,8 +3,8 @@
 // Three kernels, none of which stores the T x T matrix:
 //   vt_transpose : V [T,D] -> V^T [D,Tp] per head (zero-padded to a multiple of 64 keys), so that
 //                  the contraction index of P.V is contiguous in memory for the MFMA operands.
-//   attn_fwd     : one workgroup = 128 queries (4 waves x 32), key tiles of 64 streamed through
-//                  LDS.  The score tile is computed TRANSPOSED, S^T = K.Q^T, with
+//   attn_fwd     : one workgroup = 128 or 256 queries (4 or 8 waves x 32), key tiles of 64 double-
+//                  buffered in LDS.  The score tile is computed TRANSPOSED, S^T = K.Q^T, with
 //                  v_mfma_f32_32x32x16_bf16: in the accumulator layout a lane then owns one query
 //                  (column) and 16 keys (rows), so the row max / row sum of the online softmax are
 //                  in-lane reductions plus one exchange between the two half-waves, the rescale
