@@ -218,7 +218,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
             mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * scale_log2e;
             const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every query
             const bool grew = m_new > m_run;
-            const float corr = exp2f(m_run - m_new);
+            const float corr = __builtin_amdgcn_exp2f(m_run - m_new);  // exp2(-inf) = 0 on the first tile
             m_run = m_new;
             float psum = 0.f;
 #pragma unroll
