@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "T1", "T2", "T3", "T4"])
     ap.add_argument("--score-mode", default="layer", choices=["layer", "head"])
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -88,7 +88,7 @@ class Workload:
             self.score_calls.append((q.data_ptr(), k.data_ptr(), v.data_ptr(), self.attn_out.data_ptr(), None,
                                      self.score[l].data_ptr(), B, H, G, T, D, dtc, scale, ws_p, ws_pb))
             self.select_calls.append((self.score[l].data_ptr(), B, G, T, nA, 1, 1, self.anchor[l].data_ptr(), None, 0))
-            self.merge_calls.append((k.data_ptr(), v.data_ptr(), self.anchor[l].data_ptr(), B, H, G, T, D, nA, dtc,
+            self.merge_calls.append((k.data_ptr(), v.data_ptr(), self.anchor[l].data_ptr(), B, H, G, T, D, nA, dtc, 0,
                                      self.k_cache[l].data_ptr(), self.v_cache[l].data_ptr(), cap,
                                      self.counts[l].data_ptr(), None, self.pos[l].data_ptr()))
         # decode schedule: the retention test is pure host integer arithmetic (Alg. 1)

@@ -64,6 +64,12 @@ typedef enum {
     EC_TRUNC_ABS = 1     /* absolute location N_tl                              */
 } ec_trunc_mode;
 
+/* What ec_merge_compact stores for an anchor (Sec. 3.3 "Cache Eviction v.s. Cache Merging"; Table 3b). */
+typedef enum {
+    EC_MERGE_MEAN = 0, /* the paper's method: mean of the anchor's bucket (Eq. 3)            */
+    EC_MERGE_EVICT = 1 /* eviction-only ablation: the anchor's own row, the rest is dropped  */
+} ec_merge_mode;
+
 /* Human-readable name of a status code.  Host, pure. */
 const char* ec_status_string(int status);
 
@@ -126,12 +132,14 @@ int ec_select_anchors(const float* score, int B, int G, int T, int n_anchor, int
  *   assign           DEVICE [B,G,T] int32 bucket number of every position; may be NULL
  *   pos              DEVICE [B,G,cap] int32; entries 0..n_anchor-1 = anchor positions;
  *                    may be NULL
+ * merge_mode EC_MERGE_EVICT (the "Cache Eviction" row of Table 3b) copies the anchor rows bit for
+ * bit instead; counts are then 1 and assign is -1 for every dropped position.
  * Requires 1 <= n_anchor <= min(T, cap).  Anchors that are not strictly ascending
  * inside [0,T) give unspecified cache contents (no out-of-bounds access).
  */
 int ec_merge_compact(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G,
-                     int T, int D, int n_anchor, int dt, void* k_cache, void* v_cache, int cap,
-                     int32_t* counts, int32_t* assign, int32_t* pos, void* stream);
+                     int T, int D, int n_anchor, int dt, int merge_mode, void* k_cache, void* v_cache,
+                     int cap, int32_t* counts, int32_t* assign, int32_t* pos, void* stream);
 
 /*
  * Retention test and truncation location of the fixed-point elimination

@@ -125,6 +125,20 @@ def merge_compact(x, assign, n_anchor: int, cap: int | None = None):
     return cache
 
 
+def evict_compact(x, anchor_idx, cap: int | None = None):
+    """Eviction-only ablation (Table 3b): the anchors' own rows.  x [B,H,T,D], anchor_idx [B,G,n]."""
+    x = _f64(x)
+    B, H, T, D = x.shape
+    a = np.ascontiguousarray(anchor_idx, dtype=np.int32)
+    G, n = a.shape[1], a.shape[2]
+    cap = n if cap is None else cap
+    cache = np.zeros((B, H, cap, D), np.float64)
+    rc = _load().oracle_evict_compact(_d(x), _i(a), B, H, G, T, D, n, cap, _d(cache))
+    if rc:
+        raise ValueError(f"oracle_evict_compact rc={rc}")
+    return cache
+
+
 def evict_index(n_seen: int, len_after_append: int, gamma_num: int, gamma_den: int,
                 budget_mode: int = 0, fixed_len: int = 0, trunc_mode: int = 0, recent: int = 25,
                 n_tl: int = 0, protect_first: int = 1) -> int:

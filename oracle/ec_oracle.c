@@ -267,6 +267,26 @@ int oracle_merge_compact(const double *x, const int32_t *assign, int B, int H, i
 }
 
 /* ------------------------------------------------------------------------- */
+/* "Cache Eviction" ablation (Table 3b; Sec. 3.2 Cache Eviction v.s. Cache     */
+/* Merging): keep the anchors' own rows, drop everything else.                */
+/* x [B,H,T,D], anchor_idx [B,G,n] -> cache [B,H,cap,D] rows 0..n-1.           */
+/* ------------------------------------------------------------------------- */
+int oracle_evict_compact(const double *x, const int32_t *anchor_idx, int B, int H, int G, int T,
+                         int D, int n_anchor, int cap, double *cache)
+{
+    if (B < 1 || H < 1 || T < 1 || D < 1 || (G != 1 && G != H)) return 1;
+    if (n_anchor < 1 || n_anchor > T || cap < n_anchor) return 1;
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        const int32_t *a = anchor_idx + ((size_t)b * G + (G == 1 ? 0 : h)) * n_anchor;
+        for (int kk = 0; kk < n_anchor; ++kk)
+            for (int d = 0; d < D; ++d)
+                cache[((size_t)bh * cap + kk) * D + d] = x[((size_t)bh * T + a[kk]) * D + d];
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Retention test + truncation location (Sec. 3.3 Output Generation, Alg. 1). */
 /* n_seen: tokens seen so far including the one just appended.                */
 /* len_after_append: cache rows including the new one.                        */

@@ -19,6 +19,7 @@ EC_F32, EC_BF16 = 0, 1
 EC_FN_PREFILL_SCORE, EC_FN_SELECT_ANCHORS, EC_FN_MERGE_COMPACT, EC_FN_DECODE_STEP = range(4)
 EC_BUDGET_RATIO, EC_BUDGET_FIXED = 0, 1
 EC_TRUNC_RECENT, EC_TRUNC_ABS = 0, 1
+EC_MERGE_MEAN, EC_MERGE_EVICT = 0, 1
 
 SYMBOLS = ("ec_status_string", "ec_workspace_bytes", "ec_prefill_score", "ec_select_anchors",
            "ec_merge_compact", "ec_evict_index", "ec_decode_step")
@@ -50,7 +51,7 @@ def load():
     lib.ec_prefill_score.restype = c_int
     lib.ec_select_anchors.argtypes = [c_vp] + [c_int] * 6 + [c_vp, c_vp, c_sz, c_vp]
     lib.ec_select_anchors.restype = c_int
-    lib.ec_merge_compact.argtypes = [c_vp] * 3 + [c_int] * 7 + [c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_vp]
+    lib.ec_merge_compact.argtypes = [c_vp] * 3 + [c_int] * 8 + [c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_vp]
     lib.ec_merge_compact.restype = c_int
     lib.ec_evict_index.argtypes = [ctypes.c_int64] + [c_int] * 9
     lib.ec_evict_index.restype = c_int
@@ -120,13 +121,14 @@ def ec_select_anchors(score, n_anchor: int, protect_first: int, protect_last: in
     return rc
 
 
-def ec_merge_compact(k, v, anchor_idx, k_cache, v_cache, counts=None, assign=None, pos=None, check=True) -> int:
+def ec_merge_compact(k, v, anchor_idx, k_cache, v_cache, counts=None, assign=None, pos=None,
+                     merge_mode: int = EC_MERGE_MEAN, check=True) -> int:
     """k,v [B,H,T,D]; anchor_idx [B,G,n]; k_cache,v_cache [B,H,cap,D]."""
     B, H, T, D = k.shape
     G, n_anchor = anchor_idx.shape[1], anchor_idx.shape[2]
     cap = k_cache.shape[2]
     rc = load().ec_merge_compact(_ptr(k, "k"), _ptr(v, "v"), _ptr(anchor_idx, "anchor_idx"), B, H, G, T, D, n_anchor,
-                                 dtype_code(k), _ptr(k_cache, "k_cache"), _ptr(v_cache, "v_cache"), cap,
+                                 dtype_code(k), merge_mode, _ptr(k_cache, "k_cache"), _ptr(v_cache, "v_cache"), cap,
                                  _ptr(counts, "counts"), _ptr(assign, "assign"), _ptr(pos, "pos"), _stream())
     if check and rc != EC_OK:
         raise EcError("ec_merge_compact", rc)

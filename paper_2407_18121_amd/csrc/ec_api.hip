@@ -10,8 +10,8 @@ int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k
                     int32_t new_pos, float scale, int dt, void* out, int forced_waves, int forced_unroll,
                     hipStream_t stream);
 int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G, int T,
-                   int D, int n_anchor, int dt, void* k_cache, void* v_cache, int cap, int32_t* counts,
-                   int32_t* assign, int32_t* pos, hipStream_t stream);
+                   int D, int n_anchor, int dt, int evict_only, void* k_cache, void* v_cache, int cap,
+                   int32_t* counts, int32_t* assign, int32_t* pos, hipStream_t stream);
 int select_dispatch(const float* score, int B, int G, int T, int n_anchor, int protect_first,
                     int protect_last, int32_t* anchor_idx, hipStream_t stream);
 int score_simt_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
@@ -119,17 +119,18 @@ int ec_select_anchors(const float* score, int B, int G, int T, int n_anchor, int
 }
 
 int ec_merge_compact(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G, int T,
-                     int D, int n_anchor, int dt, void* k_cache, void* v_cache, int cap, int32_t* counts,
-                     int32_t* assign, int32_t* pos, void* stream)
+                     int D, int n_anchor, int dt, int merge_mode, void* k_cache, void* v_cache, int cap,
+                     int32_t* counts, int32_t* assign, int32_t* pos, void* stream)
 {
+    if (merge_mode != EC_MERGE_MEAN && merge_mode != EC_MERGE_EVICT) return EC_EINVAL;
     if (!k || !v || !anchor_idx || !k_cache || !v_cache) return EC_EINVAL;
     if (B < 1 || H < 1 || T < 1 || D < 1 || cap < 1) return EC_EINVAL;
     if (G != 1 && G != H) return EC_EINVAL;
     if (n_anchor < 1 || n_anchor > T || n_anchor > cap) return EC_EINVAL;
     if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
     if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
-    return ec::merge_dispatch(k, v, anchor_idx, B, H, G, T, D, n_anchor, dt, k_cache, v_cache, cap, counts,
-                              assign, pos, reinterpret_cast<hipStream_t>(stream));
+    return ec::merge_dispatch(k, v, anchor_idx, B, H, G, T, D, n_anchor, dt, merge_mode == EC_MERGE_EVICT,
+                              k_cache, v_cache, cap, counts, assign, pos, reinterpret_cast<hipStream_t>(stream));
 }
 
 int ec_evict_index(int64_t n_seen, int len_after_append, int gamma_num, int gamma_den, int budget_mode,

@@ -31,7 +31,8 @@ template <int DT, int D>
 __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     const uint4* __restrict__ k, const uint4* __restrict__ v, const int32_t* __restrict__ anchor_idx,
     uint4* __restrict__ k_cache, uint4* __restrict__ v_cache, int32_t* __restrict__ counts,
-    int32_t* __restrict__ assign, int32_t* __restrict__ pos, int H, int G, int T, int n_anchor, int cap)
+    int32_t* __restrict__ assign, int32_t* __restrict__ pos, int H, int G, int T, int n_anchor, int cap,
+    int evict_only)
 {
     constexpr int LPR = D * Elem<DT>::kBytes / 16;
     constexpr int EPL = Elem<DT>::kPerChunk;
@@ -45,6 +46,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     const int32_t* a = anchor_idx + ((size_t)b * G + (G == 1 ? 0 : h)) * n_anchor;
     int lo, hi;
     bucket_bounds(a, j, n_anchor, T, lo, hi);
+    const int blo = lo, bhi = hi;  // the bucket, for the bookkeeping
+    if (evict_only) lo = hi = min(max(a[j], 0), T - 1);  // eviction-only ablation: the anchor's own row
 
     const uint4* src = (blockIdx.z == 0 ? k : v) + (size_t)bh * T * LPR + sub;
     uint4* dst = (blockIdx.z == 0 ? k_cache : v_cache) + ((size_t)bh * cap + j) * LPR + sub;
@@ -87,32 +90,32 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
             if (pos) pos[bg * cap + j] = a[j];
         }
         if (assign)
-            for (int t = lo + sub; t <= hi; t += LPR) assign[bg * T + t] = j;
+            for (int t = blo + sub; t <= bhi; t += LPR) assign[bg * T + t] = (!evict_only || t == lo) ? j : -1;
     }
 }
 
 template <int DT, int D>
 static int launch_merge(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G,
                         int T, int n_anchor, void* k_cache, void* v_cache, int cap, int32_t* counts, int32_t* assign,
-                        int32_t* pos, hipStream_t stream)
+                        int32_t* pos, int evict_only, hipStream_t stream)
 {
     constexpr int LPR = D * Elem<DT>::kBytes / 16;
     constexpr int GROUPS = kMergeThreads / LPR;
     dim3 grid((n_anchor + GROUPS - 1) / GROUPS, B * H, 2);
     hipLaunchKernelGGL((merge_compact_kernel<DT, D>), grid, dim3(kMergeThreads), 0, stream,
                        (const uint4*)k, (const uint4*)v, anchor_idx, (uint4*)k_cache, (uint4*)v_cache,
-                       counts, assign, pos, H, G, T, n_anchor, cap);
+                       counts, assign, pos, H, G, T, n_anchor, cap, evict_only);
     return status_from_hip(hipGetLastError());
 }
 
 int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G, int T,
-                   int D, int n_anchor, int dt, void* k_cache, void* v_cache, int cap, int32_t* counts,
-                   int32_t* assign, int32_t* pos, hipStream_t stream)
+                   int D, int n_anchor, int dt, int evict_only, void* k_cache, void* v_cache, int cap,
+                   int32_t* counts, int32_t* assign, int32_t* pos, hipStream_t stream)
 {
 #define EC_MERGE_CASE(DT_, D_)                                                                      \
     if (dt == DT_ && D == D_)                                                                       \
         return launch_merge<DT_, D_>(k, v, anchor_idx, B, H, G, T, n_anchor, k_cache, v_cache, cap, counts, \
-                                     assign, pos, stream);
+                                     assign, pos, evict_only, stream);
     EC_MERGE_CASE(EC_BF16, 128)
     EC_MERGE_CASE(EC_BF16, 64)
     EC_MERGE_CASE(EC_F32, 128)

@@ -69,6 +69,11 @@ CONFIGS = {
     "C4": Config("C4", 4, 40, 40, 128, 4, 1024, "bf16", (1, 2), 512, _llava_layout(1024)),
     "C5": Config("C5", 5, 32, 32, 128, 16, 8192, "bf16", (1, 10), 1024,
                  (("t", 32),) + (("i", 576), ("t", 64)) * 12 + (("t", 480),)),
+    # shapes of the paper's own speed measurements (Table 2: budget 0.2, prompt + generated lengths)
+    "T1": Config("T1", 11, 40, 40, 128, 8, 1024, "bf16", (1, 5), 512, _llava_layout(1024)),
+    "T2": Config("T2", 12, 40, 40, 128, 16, 624, "bf16", (1, 5), 256, _llava_layout(624)),
+    "T3": Config("T3", 13, 32, 32, 128, 16, 1024, "bf16", (1, 5), 512, _llava_layout(1024)),
+    "T4": Config("T4", 14, 32, 32, 128, 48, 624, "bf16", (1, 5), 256, _llava_layout(624)),
 }
 
 

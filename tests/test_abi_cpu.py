@@ -37,7 +37,7 @@ def test_invalid_arguments_are_rejected_before_any_launch():
     lib = ec.load()
     # NULL pointers / bad shapes: the host returns before touching the device
     assert lib.ec_select_anchors(None, 1, 1, 8, 4, 1, 1, None, None, 0, None) == ec.EC_EINVAL
-    assert lib.ec_merge_compact(None, None, None, 1, 1, 1, 8, 64, 4, 0, None, None, 4, None, None, None, None) == ec.EC_EINVAL
+    assert lib.ec_merge_compact(None, None, None, 1, 1, 1, 8, 64, 4, 0, 0, None, None, 4, None, None, None, None) == ec.EC_EINVAL
     assert lib.ec_decode_step(None, None, None, None, None, None, 1, 1, 1, 64, 8, 0, -1, 0, 1.0, 0, None, None, 0, None) == ec.EC_EINVAL
     assert lib.ec_prefill_score(None, None, None, None, None, None, 1, 1, 1, 8, 64, 0, 1.0, None, 0, None) == ec.EC_EINVAL
     one = ctypes.c_void_p(256)  # never dereferenced: validation fails first
@@ -47,7 +47,8 @@ def test_invalid_arguments_are_rejected_before_any_launch():
     assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 64, 8, 3, 4, 0, 1.0, 0, one, one, 1 << 20, None) == ec.EC_EINVAL   # evict > len
     assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 96, 8, 3, 1, 0, 1.0, 0, one, one, 1 << 20, None) == ec.EC_EUNSUPPORTED
     assert lib.ec_prefill_score(one, one, one, None, None, one, 1, 1, 1, 8, 64, 0, 1.0, one, 16, None) == ec.EC_EWORKSPACE
-    assert lib.ec_merge_compact(one, one, one, 1, 4, 2, 8, 64, 4, 0, one, one, 4, None, None, None, None) == ec.EC_EINVAL  # G not in {1,H}
+    assert lib.ec_merge_compact(one, one, one, 1, 4, 2, 8, 64, 4, 0, 0, one, one, 4, None, None, None, None) == ec.EC_EINVAL  # G not in {1,H}
+    assert lib.ec_merge_compact(one, one, one, 1, 4, 1, 8, 64, 4, 0, 7, one, one, 4, None, None, None, None) == ec.EC_EINVAL  # merge_mode
 
 
 def test_evict_index_matches_oracle_everywhere():

@@ -18,14 +18,15 @@ from util import assert_close, to_host
 pytestmark = pytest.mark.gpu
 
 # config -> batch elements the oracle recomputes
-SAMPLES = {"C2": [0], "C3": [0, 5], "C4": [1], "C5": [11]}
+SAMPLES = {"C2": [0], "C3": [0, 5], "C4": [1], "C5": [11], "T1": [7], "T2": [3], "T3": [0], "T4": [40]}
+ALL = ["C2", "C3", "C4", "C5", "T1", "T2", "T3", "T4"]  # T*: the shapes the paper timed (Table 2, budget 0.2)
 
 
 def _host(t):
     return t.float().cpu().numpy()
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+@pytest.mark.parametrize("name", ALL)
 def test_prefill_chain_full_shape(name):
     cfg = syn.CONFIGS[name]
     B, H, T, D, nA, cap = cfg.B, cfg.H, cfg.T, cfg.D, cfg.n_anchor, cfg.cap
@@ -91,7 +92,7 @@ def test_prefill_chain_full_shape(name):
         assert (lhs - rhs).abs().max().item() <= 2.0 ** -8 * float((v[b].float().abs()).sum(1).max()) + 1e-2
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+@pytest.mark.parametrize("name", ALL)
 def test_decode_full_shape(name):
     cfg = syn.CONFIGS[name]
     B, H, D, cap = cfg.B, cfg.H, cfg.D, cfg.cap

@@ -114,3 +114,32 @@ def test_merge_optional_outputs_may_be_null_and_batches_are_independent():
         ec.ec_merge_compact(to_dev(k[b:b + 1], dtype), to_dev(v[b:b + 1], dtype), torch.from_numpy(a[b:b + 1]).cuda(), one_k, one_v)
         torch.cuda.synchronize()
         assert torch.equal(one_k[0], full_k[b]) and torch.equal(one_v[0], full_v[b])
+
+
+@pytest.mark.parametrize("dtype,D,Gmode", [("bf16", 128, "layer"), ("f32", 64, "head"), ("bf16", 64, "head")])
+def test_evict_only_mode_copies_anchor_rows(dtype, D, Gmode):
+    """Table 3b's eviction-only ablation: anchor rows bit for bit, counts 1, dropped positions -1."""
+    B, H, T, n, cap = 2, 4, 333, 70, 80
+    G = 1 if Gmode == "layer" else H
+    rng = np.random.default_rng(D + n)
+    k = quantize(rng.standard_normal((B, H, T, D)) * 3, dtype)
+    v = quantize(rng.standard_normal((B, H, T, D)), dtype)
+    a = _anchors(rng, B, G, T, n)
+    dk_c = torch.full((B, H, cap, D), 9.0, dtype=torch_dtype(dtype), device="cuda")
+    dv_c = torch.full((B, H, cap, D), 9.0, dtype=torch_dtype(dtype), device="cuda")
+    d_counts = torch.full((B, G, n), -7, dtype=torch.int32, device="cuda")
+    d_assign = torch.full((B, G, T), -7, dtype=torch.int32, device="cuda")
+    d_pos = torch.full((B, G, cap), -7, dtype=torch.int32, device="cuda")
+    ec.ec_merge_compact(to_dev(k, dtype), to_dev(v, dtype), torch.from_numpy(a).cuda(), dk_c, dv_c, d_counts, d_assign,
+                        d_pos, merge_mode=ec.EC_MERGE_EVICT)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host(dk_c)[:, :, :n], oracle.evict_compact(k, a))
+    np.testing.assert_array_equal(to_host(dv_c)[:, :, :n], oracle.evict_compact(v, a))
+    assert (to_host(dk_c)[:, :, n:] == 9.0).all()
+    assert (d_counts.cpu().numpy() == 1).all()
+    np.testing.assert_array_equal(d_pos.cpu().numpy()[:, :, :n], a)
+    want_assign = np.full((B, G, T), -1, np.int32)
+    for b in range(B):
+        for g in range(G):
+            want_assign[b, g, a[b, g]] = np.arange(n)
+    np.testing.assert_array_equal(d_assign.cpu().numpy(), want_assign)

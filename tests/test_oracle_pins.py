@@ -201,6 +201,21 @@ def test_merge_special_cases():
     np.testing.assert_array_equal(oracle.merge_compact(const, assign, 3), np.full((B, H, 3, D), 3.25))
 
 
+def test_evict_only_variant_is_a_gather():
+    # Table 3b "Cache Eviction": anchors keep their own vectors (library gather as the independent side)
+    B, H, T, D, n = 2, 3, 40, 5, 9
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((B, H, T, D))
+    for G in (1, H):
+        a = np.stack([np.stack([np.sort(rng.choice(T, n, replace=False)) for _ in range(G)])
+                      for _ in range(B)]).astype(np.int32)
+        got = oracle.evict_compact(x, a, cap=n + 2)
+        idx = np.broadcast_to(a if G == H else np.repeat(a, H, axis=1), (B, H, n))
+        want = np.take_along_axis(x, idx[..., None].astype(np.int64), axis=2)
+        np.testing.assert_array_equal(got[:, :, :n], want)
+        assert (got[:, :, n:] == 0).all()
+
+
 # ----------------------------------------------------------------- decode attention + removal
 def _fresh_cache(B, H, cap, D, n, seed):
     rng = np.random.default_rng(seed)
