@@ -13,7 +13,7 @@
 namespace ec {
 
 constexpr int kMergeThreads = 256;
-constexpr int kMergeUnroll = 8;  // rows in flight per bucket: long buckets are latency chains otherwise
+constexpr int kMergeUnroll = 4;  // rows of K and of V in flight per bucket (8 loads per lane)
 
 // Inclusive bounds of bucket j for ascending anchors a[0..n).  Clamped so that a
 // malformed anchor list can never index outside [0,T).
@@ -40,7 +40,11 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     const int bh = blockIdx.y;
     const int b = bh / H, h = bh % H;
     const int sub = threadIdx.x % LPR;
-    const int j = blockIdx.x * GROUPS + threadIdx.x / LPR;
+    // Long and short buckets sit at the same chunk numbers in every head, and workgroups go to the 8
+    // XCDs round-robin by linear id: rotating the chunk number by the head index keeps the heavy chunks
+    // from piling onto the same XCDs.
+    const int chunk = (blockIdx.x + blockIdx.y) % gridDim.x;
+    const int j = chunk * GROUPS + threadIdx.x / LPR;
     if (j >= n_anchor) return;
 
     const int32_t* a = anchor_idx + ((size_t)b * G + (G == 1 ? 0 : h)) * n_anchor;
@@ -49,28 +53,37 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     const int blo = lo, bhi = hi;  // the bucket, for the bookkeeping
     if (evict_only) lo = hi = min(max(a[j], 0), T - 1);  // eviction-only ablation: the anchor's own row
 
-    const uint4* src = (blockIdx.z == 0 ? k : v) + (size_t)bh * T * LPR + sub;
-    uint4* dst = (blockIdx.z == 0 ? k_cache : v_cache) + ((size_t)bh * cap + j) * LPR + sub;
+    // K and V of the bucket are streamed side by side: two independent load streams per lane
+    const uint4* src_k = k + (size_t)bh * T * LPR + sub;
+    const uint4* src_v = v + (size_t)bh * T * LPR + sub;
 
-    float acc[EPL];
+    float acc_k[EPL], acc_v[EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    for (int e = 0; e < EPL; ++e) acc_k[e] = acc_v[e] = 0.f;
 
     for (int t = lo; t <= hi; t += kMergeUnroll) {
-        uint4 c[kMergeUnroll];
+        uint4 ck[kMergeUnroll], cv[kMergeUnroll];
 #pragma unroll
         for (int u = 0; u < kMergeUnroll; ++u) {
-            c[u] = make_uint4(0, 0, 0, 0);
-            if (t + u <= hi) c[u] = src[(size_t)(t + u) * LPR];
+            ck[u] = make_uint4(0, 0, 0, 0);
+            cv[u] = make_uint4(0, 0, 0, 0);
+            if (t + u <= hi) {
+                ck[u] = src_k[(size_t)(t + u) * LPR];
+                cv[u] = src_v[(size_t)(t + u) * LPR];
+            }
         }
 #pragma unroll
         for (int u = 0; u < kMergeUnroll; ++u) {
             if (t + u <= hi) {
-                float x[EPL];
-                unpack<DT>(c[u], x);
+                float xk[EPL], xv[EPL];
+                unpack<DT>(ck[u], xk);
+                unpack<DT>(cv[u], xv);
                 const bool first = (u == 0 && t == lo);  // the sum starts from the first row, so a bucket
 #pragma unroll                                           // of one is a bit-exact copy (-0 stays -0)
-                for (int e = 0; e < EPL; ++e) acc[e] = first ? x[e] : acc[e] + x[e];
+                for (int e = 0; e < EPL; ++e) {
+                    acc_k[e] = first ? xk[e] : acc_k[e] + xk[e];
+                    acc_v[e] = first ? xv[e] : acc_v[e] + xv[e];
+                }
             }
         }
     }
@@ -78,12 +91,16 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     if (count > 1) {
         const float cf = (float)count;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] = acc[e] / cf;
+        for (int e = 0; e < EPL; ++e) {
+            acc_k[e] = acc_k[e] / cf;
+            acc_v[e] = acc_v[e] / cf;
+        }
     }
-    *dst = pack<DT>(acc);
+    k_cache[((size_t)bh * cap + j) * LPR + sub] = pack<DT>(acc_k);
+    v_cache[((size_t)bh * cap + j) * LPR + sub] = pack<DT>(acc_v);
 
     // bookkeeping, once per score group: bucket size, position of the cache row, bucket of every position
-    if (blockIdx.z == 0 && (G == H || h == 0)) {
+    if (G == H || h == 0) {
         const size_t bg = (size_t)b * G + (G == 1 ? 0 : h);
         if (sub == 0) {
             if (counts) counts[bg * n_anchor + j] = count;
@@ -101,7 +118,7 @@ static int launch_merge(const void* k, const void* v, const int32_t* anchor_idx,
 {
     constexpr int LPR = D * Elem<DT>::kBytes / 16;
     constexpr int GROUPS = kMergeThreads / LPR;
-    dim3 grid((n_anchor + GROUPS - 1) / GROUPS, B * H, 2);
+    dim3 grid((n_anchor + GROUPS - 1) / GROUPS, B * H);
     hipLaunchKernelGGL((merge_compact_kernel<DT, D>), grid, dim3(kMergeThreads), 0, stream,
                        (const uint4*)k, (const uint4*)v, anchor_idx, (uint4*)k_cache, (uint4*)v_cache,
                        counts, assign, pos, H, G, T, n_anchor, cap, evict_only);
