@@ -32,7 +32,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // 16-byte staging 
 constexpr int kMfmaThreads = 256;
 constexpr int kFwdBN = 64;   // keys per LDS tile
 constexpr int kColBN = 128;  // keys per workgroup in colsum (32 per wave)
-constexpr int kColBM = 64;   // queries per LDS tile in colsum
+constexpr int kColBM = 64;   // queries per LDS tile in colsum (128 measured slower: it halves the occupancy)
 constexpr int kVtPitch = kFwdBN + 8;  // bf16 elements per V^T row in LDS (144 B: conflict-free b128 reads)
 
 __host__ __device__ inline int padded_T(int T) { return (T + 63) / 64 * 64; }
@@ -352,60 +352,68 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
         if (more) fetch(m0 + kColBM);
 
         if (m0 + kColBM - 1 >= n0 + wave * 32) {  // else every query of the tile precedes this wave's keys
-            f32x16 s[2];
-            bf16x8 qa[2][KB];
+            constexpr int MB = kColBM / 32;  // 32-query blocks per tile
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
+            for (int mp = 0; mp < MB; mp += 2) {  // two blocks at a time: two independent MFMA chains
+                f32x16 s[2];
+                bf16x8 qa[2][KB];
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-                    qa[mb][kb] = *reinterpret_cast<const bf16x8*>(&qs[buf][(mb * 32 + c32) * QP + kb * 16 + h * 8]);
+                for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[mb][r] = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
+                    for (int mb = 0; mb < 2; ++mb)
+                        qa[mb][kb] = *reinterpret_cast<const bf16x8*>(
+                            &qs[buf][((mp + mb) * 32 + c32) * QP + kb * 16 + h * 8]);
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)
-                    s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[mb][kb], kf[kb], s[mb], 0, 0, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-            for (int i = 0; i < 2 * KB - 4; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                    for (int r = 0; r < 16; ++r) s[mb][r] = 0.f;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+                        s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[mb][kb], kf[kb], s[mb], 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+                for (int i = 0; i < 2 * KB - 4; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
 
-            // p = exp(s - lse_row), summed down the column.  Only tiles that touch the diagonal need
-            // the causal mask; the others take the three-instruction path (fma, exp, add).
-            const bool diag = m0 < n0 + wave * 32 + 31;  // some (query, key) pair of the tile has query < key
-            if (diag) {
+                // p = exp(s - lse_row), summed down the column.  Only blocks that touch the diagonal need
+                // the causal mask; the others take the three-instruction path (fma, exp, add).
+                const int mq = m0 + mp * 32;                     // first query of this pair of blocks
+                const bool diag = mq < n0 + wave * 32 + 31;      // some (query, key) pair has query < key
+                if (diag) {
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
+                    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const float4 l4 = *reinterpret_cast<const float4*>(&lse2[buf][mb * 32 + g * 8 + h * 4]);
-                        const float lr[4] = {l4.x, l4.y, l4.z, l4.w};
+                        for (int g = 0; g < 4; ++g) {
+                            const float4 l4 =
+                                *reinterpret_cast<const float4*>(&lse2[buf][(mp + mb) * 32 + g * 8 + h * 4]);
+                            const float lr[4] = {l4.x, l4.y, l4.z, l4.w};
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) {
-                            const float p = __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + t], scale_log2e, -lr[t]));
-                            const int mm = m0 + mb * 32 + g * 8 + h * 4 + t;
-                            col += (mm >= n) ? p : 0.f;  // rows beyond T carry lse = +inf, so p = 0
+                            for (int t = 0; t < 4; ++t) {
+                                const float p = __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + t], scale_log2e, -lr[t]));
+                                const int mm = mq + mb * 32 + g * 8 + h * 4 + t;
+                                col += (mm >= n) ? p : 0.f;  // rows beyond T carry lse = +inf, so p = 0
+                            }
                         }
-                    }
-            } else {
-                float c0 = 0.f, c1 = 0.f;  // two chains keep the adds off the exp latency
+                } else {
+                    float c0 = 0.f, c1 = 0.f;  // two chains keep the adds off the exp latency
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
+                    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const float4 l4 = *reinterpret_cast<const float4*>(&lse2[buf][mb * 32 + g * 8 + h * 4]);
-                        c0 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 0], scale_log2e, -l4.x));
-                        c1 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 1], scale_log2e, -l4.y));
-                        c0 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 2], scale_log2e, -l4.z));
-                        c1 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 3], scale_log2e, -l4.w));
-                    }
-                col += c0 + c1;
+                        for (int g = 0; g < 4; ++g) {
+                            const float4 l4 =
+                                *reinterpret_cast<const float4*>(&lse2[buf][(mp + mb) * 32 + g * 8 + h * 4]);
+                            c0 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 0], scale_log2e, -l4.x));
+                            c1 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 1], scale_log2e, -l4.y));
+                            c0 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 2], scale_log2e, -l4.z));
+                            c1 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 3], scale_log2e, -l4.w));
+                        }
+                    col += c0 + c1;
+                }
             }
         }
         if (more) stage(buf ^ 1);
