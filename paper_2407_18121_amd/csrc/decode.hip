@@ -82,8 +82,8 @@ __global__ __launch_bounds__(WAVES * kWave) void decode_step_kernel(
             const int r = first_row + t * TILE + u * (WAVES * RPW) + lane_row;
             if (r >= 0) {
                 const bool is_new = (r == cache_len);
-                kd[u] = is_new ? kn[sub] : kc[(size_t)r * LPR + sub];
-                vd[u] = is_new ? vn[sub] : vc[(size_t)r * LPR + sub];
+                kd[u] = load_stream(is_new ? kn + sub : kc + (size_t)r * LPR + sub);
+                vd[u] = load_stream(is_new ? vn + sub : vc + (size_t)r * LPR + sub);
             } else {
                 kd[u] = make_uint4(0, 0, 0, 0);
                 vd[u] = make_uint4(0, 0, 0, 0);

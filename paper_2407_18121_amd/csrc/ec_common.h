@@ -74,6 +74,15 @@ template <> __device__ __forceinline__ uint4 pack<EC_BF16>(const float* f)
     return c;
 }
 
+// 16-byte load of data that is read once: the non-temporal hint keeps the stream from displacing
+// cache lines, which measurably raises the rate of large one-pass reads on this chip.
+__device__ __forceinline__ uint4 load_stream(const uint4* p)
+{
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // ---- DPP cross-lane moves inside a row of 16 lanes (full rate, no LDS) ----
 template <int CTRL> __device__ __forceinline__ float dpp_mov(float x)
 {

@@ -68,8 +68,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
             ck[u] = make_uint4(0, 0, 0, 0);
             cv[u] = make_uint4(0, 0, 0, 0);
             if (t + u <= hi) {
-                ck[u] = src_k[(size_t)(t + u) * LPR];
-                cv[u] = src_v[(size_t)(t + u) * LPR];
+                ck[u] = load_stream(src_k + (size_t)(t + u) * LPR);
+                cv[u] = load_stream(src_v + (size_t)(t + u) * LPR);
             }
         }
 #pragma unroll
