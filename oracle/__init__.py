@@ -75,6 +75,22 @@ def prefill_score(q, k, v, scale: float, G: int, want_out=True, want_attn=False)
     return {"out": out, "lse": lse, "score": score, "attn": attn}
 
 
+def chunk_score(q, k, v, P: int, scale: float, G: int, want_out=True):
+    """Multi-token pass over [P cached rows | chunk].  q [B,H,Tq,D]; k,v [B,H,P+Tq,D] -> dict(out, lse, score [B,G,P+Tq])."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    B, H, Tq, D = q.shape
+    L = P + Tq
+    assert k.shape == (B, H, L, D) and v.shape == k.shape
+    out = np.empty((B, H, Tq, D), np.float64) if want_out else None
+    lse = np.empty((B, H, Tq), np.float64)
+    score = np.empty((B, G, L), np.float64)
+    rc = _load().oracle_chunk_score(_d(q), _d(k), _d(v), B, H, Tq, P, D, ctypes.c_double(scale), G,
+                                    _d(out), _d(lse), _d(score))
+    if rc:
+        raise ValueError(f"oracle_chunk_score rc={rc}")
+    return {"out": out, "lse": lse, "score": score}
+
+
 def select_anchors(score_f32, n_anchor: int, protect_first: int = 1, protect_last: int = 1):
     """Top-n_anchor positions of each [T] fp32 score row, ascending.  score [B,G,T]."""
     s = np.ascontiguousarray(score_f32, dtype=np.float32)
@@ -123,6 +139,23 @@ def merge_compact(x, assign, n_anchor: int, cap: int | None = None):
     if rc:
         raise ValueError(f"oracle_merge_compact rc={rc}")
     return cache
+
+
+def merge_weighted(x, assign, weights, n_anchor: int, cap: int | None = None):
+    """Count-weighted per-bucket mean.  x [B,H,T,D], assign/weights [B,G,T] -> (cache [B,H,cap,D], wsum [B,G,n])."""
+    x = _f64(x)
+    B, H, T, D = x.shape
+    a = np.ascontiguousarray(assign, dtype=np.int32)
+    w = np.ascontiguousarray(weights, dtype=np.int32)
+    assert a.shape == w.shape
+    G = a.shape[1]
+    cap = n_anchor if cap is None else cap
+    cache = np.zeros((B, H, cap, D), np.float64)
+    wsum = np.zeros((B, G, n_anchor), np.int32)
+    rc = _load().oracle_merge_weighted(_d(x), _i(a), _i(w), B, H, G, T, D, n_anchor, cap, _d(cache), _i(wsum))
+    if rc:
+        raise ValueError(f"oracle_merge_weighted rc={rc}")
+    return cache, wsum
 
 
 def evict_compact(x, anchor_idx, cap: int | None = None):

@@ -27,6 +27,14 @@
  *    partition 0..T-1; "nearest anchor, tie to the earlier anchor" is the same
  *    partition and is what oracle_assign_nearest computes exhaustively.
  *  - Eq. 3 mean includes the anchor's own vector, each member weight 1.
+ *  - a later multi-token pass (chat history: Sec. 3.3 applies the compression to
+ *    all concatenated inputs; Alg. 1 is entered with a non-empty past and gen_len
+ *    > 1): the chunk's queries attend the P cached rows in full and the chunk
+ *    causally; the importance of every row of [cache | chunk] is its column sum
+ *    over THIS pass's queries (Alg. 1 assigns S, it does not accumulate); rows are
+ *    merged by the plain mean of Eq. 3 over row indices of the concatenated
+ *    sequence.  A count-weighted mean (each row weighted by the number of
+ *    original tokens it already stands for) is offered beside it as an extension.
  *  - decode order: append the new row, attend over all rows, then remove one row.
  *  - retention test: evict iff the cache is longer than ceil(gamma*n) (Alg. 1's
  *    int(seq_len - n(1-r)) >= 1); truncation location = R rows before the newest
@@ -282,6 +290,120 @@ int oracle_evict_compact(const double *x, const int32_t *anchor_idx, int B, int 
         for (int kk = 0; kk < n_anchor; ++kk)
             for (int d = 0; d < D; ++d)
                 cache[((size_t)bh * cap + kk) * D + d] = x[((size_t)bh * T + a[kk]) * D + d];
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Multi-token pass over an existing compressed cache (Sec. 3.3: encoding     */
+/* covers system prompt, instruction and chat history; Alg. 1's gen_len > 1   */
+/* branch with a non-empty past: attn is gen_len x seq_len).                  */
+/*                                                                           */
+/* q [B,H,Tq,D]: the chunk's queries.  k,v [B,H,L,D], L = P + Tq: P cached     */
+/* rows followed by the chunk's own rows.  Query m sees rows n <= P + m.      */
+/* out [B,H,Tq,D] (may be NULL), lse [B,H,Tq] (may be NULL),                   */
+/* score [B,G,L]: column sums over the Tq queries (G == 1: head mean).        */
+/* ------------------------------------------------------------------------- */
+int oracle_chunk_score(const double *q, const double *k, const double *v, int B, int H, int Tq,
+                       int P, int D, double scale, int G, double *out, double *lse,
+                       double *score)
+{
+    if (B < 1 || H < 1 || Tq < 1 || P < 0 || D < 1 || (G != 1 && G != H)) return 1;
+    const int L = P + Tq;
+    double *head_imp = (double *)calloc((size_t)B * H * L, sizeof(double));
+    if (!head_imp) return 2;
+    int fail = 0;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; ++bh) {
+        const double *qh = q + (size_t)bh * Tq * D;
+        const double *kh = k + (size_t)bh * L * D;
+        const double *vh = v + (size_t)bh * L * D;
+        double *imp = head_imp + (size_t)bh * L;
+        double *row = (double *)malloc((size_t)L * sizeof(double));
+        if (!row) {
+#pragma omp atomic write
+            fail = 1;
+            continue;
+        }
+        for (int m = 0; m < Tq; ++m) {
+            const int last = P + m; /* newest row this query may see */
+            double smax = -INFINITY;
+            for (int n = 0; n <= last; ++n) {
+                double dot = 0.0;
+                for (int d = 0; d < D; ++d) dot += qh[(size_t)m * D + d] * kh[(size_t)n * D + d];
+                row[n] = scale * dot;
+                if (row[n] > smax) smax = row[n];
+            }
+            double denom = 0.0;
+            for (int n = 0; n <= last; ++n) {
+                row[n] = exp(row[n] - smax);
+                denom += row[n];
+            }
+            if (lse) lse[(size_t)bh * Tq + m] = smax + log(denom);
+            for (int n = 0; n <= last; ++n) {
+                row[n] /= denom;
+                imp[n] += row[n];
+            }
+            if (out) {
+                double *o = out + ((size_t)bh * Tq + m) * D;
+                for (int d = 0; d < D; ++d) o[d] = 0.0;
+                for (int n = 0; n <= last; ++n)
+                    for (int d = 0; d < D; ++d) o[d] += row[n] * vh[(size_t)n * D + d];
+            }
+        }
+        free(row);
+    }
+
+    if (!fail) {
+        if (G == H) {
+            memcpy(score, head_imp, (size_t)B * H * L * sizeof(double));
+        } else {
+            for (int b = 0; b < B; ++b)
+                for (int n = 0; n < L; ++n) {
+                    double acc = 0.0;
+                    for (int h = 0; h < H; ++h) acc += head_imp[((size_t)b * H + h) * L + n];
+                    score[(size_t)b * L + n] = acc / (double)H;
+                }
+        }
+    }
+    free(head_imp);
+    return fail ? 2 : 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Count-weighted merge (extension beside Eq. 3, for re-merging rows that      */
+/* already stand for several tokens): cache row k = sum_t w_t x_t / sum_t w_t  */
+/* over the rows t of bucket k.  x [B,H,T,D], assign [B,G,T], w [B,G,T] int32  */
+/* positive weights -> cache [B,H,cap,D] rows 0..n_anchor-1 and                */
+/* wsum [B,G,n_anchor] (may be NULL).  With every w = 1 this is Eq. 3.         */
+/* ------------------------------------------------------------------------- */
+int oracle_merge_weighted(const double *x, const int32_t *assign, const int32_t *w, int B, int H,
+                          int G, int T, int D, int n_anchor, int cap, double *cache,
+                          int32_t *wsum)
+{
+    if (B < 1 || H < 1 || T < 1 || D < 1 || (G != 1 && G != H)) return 1;
+    if (n_anchor < 1 || n_anchor > T || cap < n_anchor) return 1;
+    for (int bh = 0; bh < B * H; ++bh) {
+        int b = bh / H, h = bh % H;
+        size_t bg = (size_t)b * G + (G == 1 ? 0 : h);
+        const int32_t *as = assign + bg * T;
+        const int32_t *wt = w + bg * T;
+        const double *xh = x + (size_t)bh * T * D;
+        double *ch = cache + (size_t)bh * cap * D;
+        for (int kk = 0; kk < n_anchor; ++kk) {
+            double *row = ch + (size_t)kk * D;
+            long long tot = 0;
+            for (int d = 0; d < D; ++d) row[d] = 0.0;
+            for (int t = 0; t < T; ++t) {
+                if (as[t] != kk) continue;
+                if (wt[t] < 1) return 1;
+                for (int d = 0; d < D; ++d) row[d] += (double)wt[t] * xh[(size_t)t * D + d];
+                tot += wt[t];
+            }
+            for (int d = 0; d < D; ++d) row[d] /= (double)tot;
+            if (wsum && (G == H || h == 0)) wsum[bg * n_anchor + kk] = (int32_t)tot;
+        }
     }
     return 0;
 }

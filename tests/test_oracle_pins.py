@@ -313,3 +313,105 @@ def test_evict_index_modes_and_edges():
     assert oracle.evict_index(3, 2, 1, 2, recent=25, protect_first=1) == -1   # within budget
     assert oracle.evict_index(2, 2, 1, 2, recent=25, protect_first=1) == -1   # only the newest row is left
     assert oracle.evict_index(10, 7, 1, 2, budget_mode=1, fixed_len=3, trunc_mode=1, n_tl=6) == -1
+
+
+# ----------------------------------------------------------------- multi-token pass over an existing cache
+@pytest.mark.parametrize("B,H,Tq,P,D,scale", [(2, 3, 9, 7, 5, 0.37), (1, 2, 5, 20, 8, 1.0), (1, 2, 12, 0, 4, 0.5),
+                                               (1, 1, 1, 13, 6, 0.7)])
+def test_chunk_score_against_library_attention(B, H, Tq, P, D, scale):
+    # Alg. 1's multi-token branch with a past: attn is Tq x (P+Tq), query m sees rows n <= P+m
+    L = P + Tq
+    q, k, v = _rand((B, H, Tq, D), 31), _rand((B, H, L, D), 32, 1.5), _rand((B, H, L, D), 33)
+    r = oracle.chunk_score(q, k, v, P, scale, H)
+    tq, tk, tv = (torch.from_numpy(x) for x in (q, k, v))
+    mask = torch.arange(L)[None, :] <= (P + torch.arange(Tq))[:, None]
+    ref_out = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, scale=scale)
+    np.testing.assert_allclose(r["out"], ref_out.numpy(), atol=1e-12)
+    s = (scale * torch.einsum("bhmd,bhnd->bhmn", tq, tk)).masked_fill(~mask, float("-inf"))
+    np.testing.assert_allclose(r["lse"], torch.logsumexp(s, -1).numpy(), atol=1e-12)
+    A = torch.softmax(s, -1)
+    np.testing.assert_allclose(r["score"], A.sum(-2).numpy(), atol=1e-12)
+    r1 = oracle.chunk_score(q, k, v, P, scale, 1)
+    np.testing.assert_allclose(r1["score"][:, 0], A.sum(-2).mean(1).numpy(), atol=1e-12)
+
+
+def test_chunk_score_closed_form_zero_queries():
+    # q = 0 -> A_mn = 1/(P+m+1) for n <= P+m -> I_n = H_{P+Tq} - H_{max(n,P)} (harmonic numbers)
+    Tq, P, D, H = 23, 11, 4, 2
+    L = P + Tq
+    q = np.zeros((1, H, Tq, D))
+    k, v = _rand((1, H, L, D), 34), _rand((1, H, L, D), 35)
+    r = oracle.chunk_score(q, k, v, P, 0.5, 1)
+    harm = np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, L + 1))])
+    expect = harm[L] - harm[np.maximum(np.arange(L), P)]
+    np.testing.assert_allclose(r["score"][0, 0], expect, atol=1e-13)
+    run_mean = (np.cumsum(v, axis=2) / np.arange(1, L + 1)[None, None, :, None])[:, :, P:]
+    np.testing.assert_allclose(r["out"], run_mean, atol=1e-13)
+    np.testing.assert_allclose(r["score"].sum(-1), Tq, rtol=1e-13)  # every query row sums to 1
+
+
+def test_chunk_score_is_the_tail_of_the_square_pass():
+    # the chunk's queries are the last Tq rows of a causal pass over all P+Tq rows
+    B, H, Tq, P, D = 1, 2, 10, 14, 6
+    L = P + Tq
+    qa, k, v = _rand((B, H, L, D), 36), _rand((B, H, L, D), 37), _rand((B, H, L, D), 38)
+    full = oracle.prefill_score(qa, k, v, 0.4, H, want_attn=True)
+    r = oracle.chunk_score(qa[:, :, P:], k, v, P, 0.4, H)
+    np.testing.assert_allclose(r["out"], full["out"][:, :, P:], atol=1e-13)
+    np.testing.assert_allclose(r["lse"], full["lse"][:, :, P:], atol=1e-13)
+    np.testing.assert_allclose(r["score"], full["attn"][:, :, P:, :].sum(-2), atol=1e-13)
+    # P = 0 is the first-turn pass itself
+    r0 = oracle.chunk_score(qa, k, v, 0, 0.4, 1)
+    f0 = oracle.prefill_score(qa, k, v, 0.4, 1)
+    np.testing.assert_allclose(r0["score"], f0["score"], atol=1e-13)
+
+
+def test_chunk_score_single_query_is_decode_attention():
+    # Tq = 1: one query over P cached rows + its own row = the generation step's attention
+    B, H, P, D = 2, 3, 17, 8
+    q, k, v = _rand((B, H, 1, D), 39), _rand((B, H, P + 1, D), 40), _rand((B, H, P + 1, D), 41)
+    r = oracle.chunk_score(q, k, v, P, 0.3, H)
+    kc = np.zeros((B, H, P + 2, D)); vc = np.zeros_like(kc)
+    kc[:, :, :P] = k[:, :, :P]; vc[:, :, :P] = v[:, :, :P]
+    out, probs = oracle.decode_step(q[:, :, 0], k[:, :, P], v[:, :, P], kc, vc, None, P, -1, 0, 0.3, want_probs=True)
+    np.testing.assert_allclose(r["out"][:, :, 0], out, atol=1e-13)
+    np.testing.assert_allclose(r["score"], probs, atol=1e-13)
+
+
+# ----------------------------------------------------------------- count-weighted re-merge
+def test_merge_weighted_unit_weights_is_eq3():
+    B, H, T, D, n = 2, 3, 40, 5, 9
+    x = _rand((B, H, T, D), 42)
+    rng = np.random.default_rng(43)
+    a = np.stack([np.sort(rng.choice(T, n, replace=False)) for _ in range(B)]).astype(np.int32).reshape(B, 1, n)
+    assign, counts = oracle.assign_nearest(a, T)
+    cache, wsum = oracle.merge_weighted(x, assign, np.ones_like(assign), n)
+    np.testing.assert_array_equal(wsum, counts)
+    lo, _ = oracle.bucket_bounds(a, T)
+    for b in range(B):
+        ref = np.add.reduceat(x[b], lo[b, 0], axis=1) / counts[b, 0][None, :, None]
+        np.testing.assert_allclose(cache[b], ref, atol=1e-13)
+
+
+def test_merge_weighted_two_levels_equal_one_level():
+    # Merging means with their counts as weights equals merging the original rows into the union
+    # buckets directly (the weighted mean is associative); the plain mean of means is not.
+    B, H, T, D = 1, 2, 60, 4
+    x = _rand((B, H, T, D), 44)
+    a1 = np.array([0, 3, 4, 10, 11, 12, 30, 31, 45, 59], np.int32).reshape(1, 1, -1)
+    n1 = a1.shape[-1]
+    assign1, counts1 = oracle.assign_nearest(a1, T)
+    level1 = oracle.merge_compact(x, assign1, n1)
+    a2 = np.array([0, 2, 5, 9], np.int32).reshape(1, 1, -1)  # anchors among the n1 level-1 rows
+    assign2, _ = oracle.assign_nearest(a2, n1)
+    level2, wsum = oracle.merge_weighted(level1, assign2, counts1, 4)
+    # union buckets: original position t -> level-1 bucket -> level-2 bucket
+    direct_assign = assign2[0, 0][assign1[0, 0]].reshape(1, 1, T)
+    direct = oracle.merge_compact(x, direct_assign, 4)
+    np.testing.assert_allclose(level2, direct, atol=1e-13)
+    np.testing.assert_array_equal(wsum[0, 0], np.bincount(direct_assign[0, 0], minlength=4))
+    assert wsum.sum() == T
+    plain = oracle.merge_compact(level1, assign2, 4)
+    assert np.abs(plain - direct).max() > 1e-3  # the unweighted mean of means differs
+    # first moment conservation: sum_k wsum_k * row_k = sum_t x_t
+    np.testing.assert_allclose((level2 * wsum[0, 0][None, None, :, None]).sum(2), x.sum(2), atol=1e-12)
