@@ -102,6 +102,32 @@ int ec_prefill_score(const void* q, const void* k, const void* v, void* out, flo
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Instruction encoding of a later chunk over an existing compressed cache (Sec. 3.3: the compression is
+ * applied to all concatenated inputs, chat history included; Alg. 1's multi-token branch entered with a
+ * non-empty past, where the attention matrix is gen_len x seq_len).  For every head, k and v hold the P
+ * rows of the compressed cache followed by the T_new rows of the chunk, in a buffer whose heads are
+ * kv_rows rows apart (kv_rows >= P + T_new; rows beyond P + T_new are never read).  Query m of the chunk
+ * (0-based) attends rows n <= P + m:
+ *     A     = row-softmax over n <= P + m of scale * <q_m, k_n>      (T_new x (P + T_new), never stored)
+ *     out_m, lse_m as in ec_prefill_score
+ *     I_n   = sum over m >= max(0, n - P) of A_mn, for every row n of [cache | chunk]
+ * The scores are this pass's column sums (Alg. 1 assigns its score buffer in this branch, it does not
+ * accumulate over passes).  score[b,g,n] is I_n of head g (G == H) or the head mean (G == 1).
+ *   q      DEVICE [B,H,T_new,D] dt, read only
+ *   k,v    DEVICE [B,H,kv_rows,D] dt, read only
+ *   out    DEVICE [B,H,T_new,D] dt, written; may be NULL
+ *   lse    DEVICE [B,H,T_new] float, written; may be NULL
+ *   score  DEVICE [B,G,P+T_new] float, written
+ *   ws     DEVICE scratch, ec_workspace_bytes(EC_FN_PREFILL_SCORE, B,H, P+T_new, D,dt)
+ * P = 0 and kv_rows = T_new is ec_prefill_score itself; T_new = 1 is one generation step's attention.
+ * Anchors are then chosen with ec_select_anchors over the P + T_new rows and the rows merged with
+ * ec_remerge_compact.
+ */
+int ec_chunk_score(const void* q, const void* k, const void* v, void* out, float* lse, float* score,
+                   int B, int H, int G, int T_new, int P, int kv_rows, int D, int dt, float scale,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Anchor selection (Sec. 3.3: "top N_I tokens in I_n, indices in ascending
  * order"; Sec. 4.1: the first and the most recent token are protected).
  * For every (b,g): positions 0..protect_first-1 and T-protect_last..T-1 are
@@ -140,6 +166,27 @@ int ec_select_anchors(const float* score, int B, int G, int T, int n_anchor, int
 int ec_merge_compact(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G,
                      int T, int D, int n_anchor, int dt, int merge_mode, void* k_cache, void* v_cache,
                      int cap, int32_t* counts, int32_t* assign, int32_t* pos, void* stream);
+
+/*
+ * ec_merge_compact for rows that may already be merged (Sec. 3.3, Eq. 2 and Eq. 3 applied again to
+ * [compressed cache | new chunk]; Alg. 1 runs the same gather / scatter_reduce / gather on whatever the
+ * cache holds).  Buckets are formed over ROW INDICES 0..L-1 of the source buffer exactly as in
+ * ec_merge_compact.  Differences:
+ *   src_rows   rows between the heads of k and v (>= L): the source may be a cache buffer with spare rows
+ *   weights    DEVICE [B,G,L] int32 or NULL.  NULL: every row weighs 1 -- the plain mean of Alg. 1, which
+ *              for rows that are themselves means is a mean of means.  Given (an extension beside the
+ *              paper): row t weighs weights[t] >= 1 (values below 1 are taken as 1), the number of
+ *              original tokens it stands for; cache row j = sum w_t x_t / sum w_t over bucket j, which is
+ *              the mean of the original tokens, and counts[j] = sum w_t.  Ignored by EC_MERGE_EVICT.
+ *   src_pos    DEVICE [B,G,L] int32 or NULL: original position of every source row; pos[j] is then
+ *              src_pos[anchor_j] instead of anchor_j
+ * k_cache / v_cache must not be k / v (rows are written while others are still being read).
+ * Everything else is as in ec_merge_compact, which is this call with src_rows = T and both NULL.
+ */
+int ec_remerge_compact(const void* k, const void* v, int src_rows, const int32_t* weights,
+                       const int32_t* src_pos, const int32_t* anchor_idx, int B, int H, int G, int L,
+                       int D, int n_anchor, int dt, int merge_mode, void* k_cache, void* v_cache, int cap,
+                       int32_t* counts, int32_t* assign, int32_t* pos, void* stream);
 
 /*
  * Retention test and truncation location of the fixed-point elimination

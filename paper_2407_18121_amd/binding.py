@@ -21,8 +21,8 @@ EC_BUDGET_RATIO, EC_BUDGET_FIXED = 0, 1
 EC_TRUNC_RECENT, EC_TRUNC_ABS = 0, 1
 EC_MERGE_MEAN, EC_MERGE_EVICT = 0, 1
 
-SYMBOLS = ("ec_status_string", "ec_workspace_bytes", "ec_prefill_score", "ec_select_anchors",
-           "ec_merge_compact", "ec_evict_index", "ec_decode_step")
+SYMBOLS = ("ec_status_string", "ec_workspace_bytes", "ec_prefill_score", "ec_chunk_score", "ec_select_anchors",
+           "ec_merge_compact", "ec_remerge_compact", "ec_evict_index", "ec_decode_step")
 
 _lib = None
 
@@ -49,10 +49,15 @@ def load():
     lib.ec_workspace_bytes.restype = c_sz
     lib.ec_prefill_score.argtypes = [c_vp] * 6 + [c_int] * 6 + [c_f, c_vp, c_sz, c_vp]
     lib.ec_prefill_score.restype = c_int
+    lib.ec_chunk_score.argtypes = [c_vp] * 6 + [c_int] * 8 + [c_f, c_vp, c_sz, c_vp]
+    lib.ec_chunk_score.restype = c_int
     lib.ec_select_anchors.argtypes = [c_vp] + [c_int] * 6 + [c_vp, c_vp, c_sz, c_vp]
     lib.ec_select_anchors.restype = c_int
     lib.ec_merge_compact.argtypes = [c_vp] * 3 + [c_int] * 8 + [c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_vp]
     lib.ec_merge_compact.restype = c_int
+    lib.ec_remerge_compact.argtypes = ([c_vp, c_vp, c_int, c_vp, c_vp, c_vp] + [c_int] * 8
+                                       + [c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_vp])
+    lib.ec_remerge_compact.restype = c_int
     lib.ec_evict_index.argtypes = [ctypes.c_int64] + [c_int] * 9
     lib.ec_evict_index.restype = c_int
     lib.ec_decode_step.argtypes = ([c_vp] * 6 + [c_int] * 7 + [ctypes.c_int32, c_f, c_int, c_vp, c_vp, c_sz, c_vp])
@@ -111,6 +116,21 @@ def ec_prefill_score(q, k, v, out, lse, score, scale: float, ws, check=True) -> 
     return rc
 
 
+def ec_chunk_score(q, k, v, P: int, out, lse, score, scale: float, ws, check=True) -> int:
+    """q [B,H,T_new,D]; k,v [B,H,kv_rows,D] holding P cached rows then the chunk's rows; score [B,G,P+T_new]."""
+    B, H, T_new, D = q.shape
+    kv_rows = k.shape[2]
+    G = score.shape[1]
+    if k.shape != v.shape or k.shape[:2] != q.shape[:2] or k.shape[3] != D or score.shape[2] != P + T_new:
+        raise ValueError("ec_chunk_score: inconsistent shapes")
+    rc = load().ec_chunk_score(_ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(out, "out"), _ptr(lse, "lse"),
+                               _ptr(score, "score"), B, H, G, T_new, P, kv_rows, D, dtype_code(q), scale,
+                               _ptr(ws, "ws"), 0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    if check and rc != EC_OK:
+        raise EcError("ec_chunk_score", rc)
+    return rc
+
+
 def ec_select_anchors(score, n_anchor: int, protect_first: int, protect_last: int, anchor_idx, check=True) -> int:
     """score [B,G,T] f32 -> anchor_idx [B,G,n_anchor] int32 ascending."""
     B, G, T = score.shape
@@ -132,6 +152,25 @@ def ec_merge_compact(k, v, anchor_idx, k_cache, v_cache, counts=None, assign=Non
                                  _ptr(counts, "counts"), _ptr(assign, "assign"), _ptr(pos, "pos"), _stream())
     if check and rc != EC_OK:
         raise EcError("ec_merge_compact", rc)
+    return rc
+
+
+def ec_remerge_compact(k, v, L: int, anchor_idx, k_cache, v_cache, weights=None, src_pos=None, counts=None,
+                       assign=None, pos=None, merge_mode: int = EC_MERGE_MEAN, check=True) -> int:
+    """k,v [B,H,src_rows,D] of which rows 0..L-1 are merged; weights, src_pos [B,G,L] int32 or None."""
+    B, H, src_rows, D = k.shape
+    G, n_anchor = anchor_idx.shape[1], anchor_idx.shape[2]
+    cap = k_cache.shape[2]
+    for name, t in (("weights", weights), ("src_pos", src_pos)):
+        if t is not None and tuple(t.shape) != (B, G, L):
+            raise ValueError(f"ec_remerge_compact: {name} must be [B,G,L]")
+    rc = load().ec_remerge_compact(_ptr(k, "k"), _ptr(v, "v"), src_rows, _ptr(weights, "weights"),
+                                   _ptr(src_pos, "src_pos"), _ptr(anchor_idx, "anchor_idx"), B, H, G, L, D,
+                                   n_anchor, dtype_code(k), merge_mode, _ptr(k_cache, "k_cache"),
+                                   _ptr(v_cache, "v_cache"), cap, _ptr(counts, "counts"), _ptr(assign, "assign"),
+                                   _ptr(pos, "pos"), _stream())
+    if check and rc != EC_OK:
+        raise EcError("ec_remerge_compact", rc)
     return rc
 
 

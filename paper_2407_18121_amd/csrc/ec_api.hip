@@ -9,16 +9,17 @@ int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k
                     int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
                     int32_t new_pos, float scale, int dt, void* out, int forced_waves, int forced_unroll,
                     hipStream_t stream);
-int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G, int T,
-                   int D, int n_anchor, int dt, int evict_only, void* k_cache, void* v_cache, int cap,
-                   int32_t* counts, int32_t* assign, int32_t* pos, hipStream_t stream);
+int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, const int32_t* weights,
+                   const int32_t* src_pos, int B, int H, int G, int T, int src_rows, int D, int n_anchor, int dt,
+                   int evict_only, void* k_cache, void* v_cache, int cap, int32_t* counts, int32_t* assign,
+                   int32_t* pos, hipStream_t stream);
 int select_dispatch(const float* score, int B, int G, int T, int n_anchor, int protect_first,
                     int protect_last, int32_t* anchor_idx, hipStream_t stream);
 int score_simt_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
-                        float* head_imp, int B, int H, int T, int D, int dt, float scale,
+                        float* head_imp, int B, int H, ScoreGeom geo, int D, int dt, float scale,
                         hipStream_t stream);
 int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
-                        float* head_imp, void* vt, int B, int H, int T, int D, int dt, float scale,
+                        float* head_imp, void* vt, int B, int H, ScoreGeom geo, int D, int dt, float scale,
                         int forced_waves, hipStream_t stream);
 size_t score_mfma_vt_bytes(int B, int H, int T, int D);
 int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, hipStream_t stream);
@@ -35,6 +36,41 @@ int env_int(const char* name, int dflt)
 {
     const char* s = std::getenv(name);
     return s ? std::atoi(s) : dflt;
+}
+
+// Scoring pass of either entry point: Tq queries over L = P + Tq rows, heads of k/v kv_rows rows apart.
+int score_pass(const void* q, const void* k, const void* v, void* out, float* lse, float* score, int B, int H,
+               int G, ec::ScoreGeom geo, int D, int dt, float scale, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!q || !k || !v || !score) return EC_EINVAL;
+    if (B < 1 || H < 1 || geo.Tq < 1 || geo.P < 0 || D < 1) return EC_EINVAL;
+    if (geo.kv_rows < geo.L) return EC_EINVAL;
+    if (G != 1 && G != H) return EC_EINVAL;
+    if (!(scale == scale)) return EC_EINVAL;
+    if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
+    if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
+    const size_t need = ec_workspace_bytes(EC_FN_PREFILL_SCORE, B, H, geo.L, D, dt);
+    if (need == (size_t)-1) return EC_EUNSUPPORTED;
+    if (!ws || ws_bytes < need) return EC_EWORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+
+    const size_t stat_bytes = align256((size_t)B * H * geo.L * sizeof(float));
+    float* ws_imp = reinterpret_cast<float*>(ws);
+    float* ws_lse = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + stat_bytes);
+    void* ws_vt = reinterpret_cast<char*>(ws) + 2 * stat_bytes;
+    float* lse_buf = lse ? lse : ws_lse;
+    float* head_imp = (G == H) ? score : ws_imp;
+
+    int rc;
+    const bool use_mfma = (dt == EC_BF16) && !env_int("EC_SCORE_FORCE_SIMT", 0);
+    if (use_mfma)
+        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, ws_vt, B, H, geo, D, dt, scale,
+                                     env_int("EC_SCORE_WAVES", 0), s);
+    else
+        rc = ec::score_simt_dispatch(q, k, v, out, lse_buf, head_imp, B, H, geo, D, dt, scale, s);
+    if (rc != EC_OK) return rc;
+    if (G == 1) rc = ec::head_mean_launch(head_imp, score, B, H, geo.L, s);
+    return rc;
 }
 
 }  // namespace
@@ -75,33 +111,18 @@ int ec_prefill_score(const void* q, const void* k, const void* v, void* out, flo
                      int B, int H, int G, int T, int D, int dt, float scale, void* ws, size_t ws_bytes,
                      void* stream)
 {
-    if (!q || !k || !v || !score) return EC_EINVAL;
-    if (B < 1 || H < 1 || T < 1 || D < 1) return EC_EINVAL;
-    if (G != 1 && G != H) return EC_EINVAL;
-    if (!(scale == scale)) return EC_EINVAL;
-    if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
-    if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
-    const size_t need = ec_workspace_bytes(EC_FN_PREFILL_SCORE, B, H, T, D, dt);
-    if (!ws || ws_bytes < need) return EC_EWORKSPACE;
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (T < 1) return EC_EINVAL;
+    return score_pass(q, k, v, out, lse, score, B, H, G, ec::ScoreGeom{T, 0, T, T}, D, dt, scale, ws, ws_bytes,
+                      stream);
+}
 
-    const size_t stat_bytes = align256((size_t)B * H * T * sizeof(float));
-    float* ws_imp = reinterpret_cast<float*>(ws);
-    float* ws_lse = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + stat_bytes);
-    void* ws_vt = reinterpret_cast<char*>(ws) + 2 * stat_bytes;
-    float* lse_buf = lse ? lse : ws_lse;
-    float* head_imp = (G == H) ? score : ws_imp;
-
-    int rc;
-    const bool use_mfma = (dt == EC_BF16) && !env_int("EC_SCORE_FORCE_SIMT", 0);
-    if (use_mfma)
-        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, ws_vt, B, H, T, D, dt, scale,
-                                     env_int("EC_SCORE_WAVES", 0), s);
-    else
-        rc = ec::score_simt_dispatch(q, k, v, out, lse_buf, head_imp, B, H, T, D, dt, scale, s);
-    if (rc != EC_OK) return rc;
-    if (G == 1) rc = ec::head_mean_launch(head_imp, score, B, H, T, s);
-    return rc;
+int ec_chunk_score(const void* q, const void* k, const void* v, void* out, float* lse, float* score, int B,
+                   int H, int G, int T_new, int P, int kv_rows, int D, int dt, float scale, void* ws,
+                   size_t ws_bytes, void* stream)
+{
+    if (T_new < 1 || P < 0 || (long long)P + T_new > 0x7fffffffLL / 2) return EC_EINVAL;
+    return score_pass(q, k, v, out, lse, score, B, H, G, ec::ScoreGeom{T_new, P, P + T_new, kv_rows}, D, dt,
+                      scale, ws, ws_bytes, stream);
 }
 
 int ec_select_anchors(const float* score, int B, int G, int T, int n_anchor, int protect_first,
@@ -122,15 +143,26 @@ int ec_merge_compact(const void* k, const void* v, const int32_t* anchor_idx, in
                      int D, int n_anchor, int dt, int merge_mode, void* k_cache, void* v_cache, int cap,
                      int32_t* counts, int32_t* assign, int32_t* pos, void* stream)
 {
+    return ec_remerge_compact(k, v, T, nullptr, nullptr, anchor_idx, B, H, G, T, D, n_anchor, dt, merge_mode,
+                              k_cache, v_cache, cap, counts, assign, pos, stream);
+}
+
+int ec_remerge_compact(const void* k, const void* v, int src_rows, const int32_t* weights,
+                       const int32_t* src_pos, const int32_t* anchor_idx, int B, int H, int G, int L, int D,
+                       int n_anchor, int dt, int merge_mode, void* k_cache, void* v_cache, int cap,
+                       int32_t* counts, int32_t* assign, int32_t* pos, void* stream)
+{
     if (merge_mode != EC_MERGE_MEAN && merge_mode != EC_MERGE_EVICT) return EC_EINVAL;
     if (!k || !v || !anchor_idx || !k_cache || !v_cache) return EC_EINVAL;
-    if (B < 1 || H < 1 || T < 1 || D < 1 || cap < 1) return EC_EINVAL;
+    if (k == k_cache || v == v_cache || k == v_cache || v == k_cache) return EC_EINVAL;  // out of place only
+    if (B < 1 || H < 1 || L < 1 || D < 1 || cap < 1 || src_rows < L) return EC_EINVAL;
     if (G != 1 && G != H) return EC_EINVAL;
-    if (n_anchor < 1 || n_anchor > T || n_anchor > cap) return EC_EINVAL;
+    if (n_anchor < 1 || n_anchor > L || n_anchor > cap) return EC_EINVAL;
     if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
     if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
-    return ec::merge_dispatch(k, v, anchor_idx, B, H, G, T, D, n_anchor, dt, merge_mode == EC_MERGE_EVICT,
-                              k_cache, v_cache, cap, counts, assign, pos, reinterpret_cast<hipStream_t>(stream));
+    return ec::merge_dispatch(k, v, anchor_idx, weights, src_pos, B, H, G, L, src_rows, D, n_anchor, dt,
+                              merge_mode == EC_MERGE_EVICT, k_cache, v_cache, cap, counts, assign, pos,
+                              reinterpret_cast<hipStream_t>(stream));
 }
 
 int ec_evict_index(int64_t n_seen, int len_after_append, int gamma_num, int gamma_den, int budget_mode,

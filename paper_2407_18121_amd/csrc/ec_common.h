@@ -116,6 +116,13 @@ __device__ __forceinline__ float wave_max(float x)
     return x;
 }
 
+// Geometry of one scoring pass.  Every head of k/v holds P rows of an existing compressed cache followed
+// by the Tq rows of the chunk being encoded (L = P + Tq rows), heads kv_rows rows apart.  Query m of the
+// chunk sees rows n <= P + m.  The first-turn pass over a bare prompt is P = 0, kv_rows = Tq.
+struct ScoreGeom {
+    int Tq, P, L, kv_rows;
+};
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 

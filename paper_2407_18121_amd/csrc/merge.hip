@@ -1,5 +1,5 @@
-// ec_merge_compact: bucket division (Sec. 3.3, Eq. 2), cache merging (Eq. 3) and
-// compaction (Alg. 1's gather) in one pass over K and V.
+// ec_merge_compact / ec_remerge_compact: bucket division (Sec. 3.3, Eq. 2), cache merging
+// (Eq. 3) and compaction (Alg. 1's gather) in one pass over K and V.
 //
 // HBM-bound: every prompt K/V row is read once, every cache row written once.
 // Buckets are contiguous position ranges, so the rows of bucket j are one
@@ -27,12 +27,17 @@ __device__ __forceinline__ void bucket_bounds(const int32_t* __restrict__ a, int
     hi = min(hi, T - 1);
 }
 
-template <int DT, int D>
+// WEIGHTED: every source row t carries an integer weight w_t (the number of original tokens it already
+// stands for, when rows of an earlier merge are merged again); the cache row is sum w_t x_t / sum w_t
+// and counts receives sum w_t.  Without it every row weighs 1 (Eq. 3).  src_rows is the distance in rows
+// between the heads of k/v (>= T); src_pos, if given, maps a source row to its original position.
+template <int DT, int D, bool WEIGHTED>
 __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     const uint4* __restrict__ k, const uint4* __restrict__ v, const int32_t* __restrict__ anchor_idx,
+    const int32_t* __restrict__ weights, const int32_t* __restrict__ src_pos,
     uint4* __restrict__ k_cache, uint4* __restrict__ v_cache, int32_t* __restrict__ counts,
-    int32_t* __restrict__ assign, int32_t* __restrict__ pos, int H, int G, int T, int n_anchor, int cap,
-    int evict_only)
+    int32_t* __restrict__ assign, int32_t* __restrict__ pos, int H, int G, int T, int src_rows, int n_anchor,
+    int cap, int evict_only)
 {
     constexpr int LPR = D * Elem<DT>::kBytes / 16;
     constexpr int EPL = Elem<DT>::kPerChunk;
@@ -47,27 +52,35 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     const int j = chunk * GROUPS + threadIdx.x / LPR;
     if (j >= n_anchor) return;
 
-    const int32_t* a = anchor_idx + ((size_t)b * G + (G == 1 ? 0 : h)) * n_anchor;
+    const size_t bg = (size_t)b * G + (G == 1 ? 0 : h);
+    const int32_t* a = anchor_idx + bg * n_anchor;
+    const int32_t* wrow = WEIGHTED ? weights + bg * T : nullptr;
     int lo, hi;
     bucket_bounds(a, j, n_anchor, T, lo, hi);
     const int blo = lo, bhi = hi;  // the bucket, for the bookkeeping
     if (evict_only) lo = hi = min(max(a[j], 0), T - 1);  // eviction-only ablation: the anchor's own row
 
     // K and V of the bucket are streamed side by side: two independent load streams per lane
-    const uint4* src_k = k + (size_t)bh * T * LPR + sub;
-    const uint4* src_v = v + (size_t)bh * T * LPR + sub;
+    const uint4* src_k = k + (size_t)bh * src_rows * LPR + sub;
+    const uint4* src_v = v + (size_t)bh * src_rows * LPR + sub;
 
     float acc_k[EPL], acc_v[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc_k[e] = acc_v[e] = 0.f;
 
+    // a bucket of one row is copied (weight 1 whatever it carries), so it stays bit-exact
+    const bool use_w = WEIGHTED && hi > lo;
+    int wsum = 0;
     for (int t = lo; t <= hi; t += kMergeUnroll) {
         uint4 ck[kMergeUnroll], cv[kMergeUnroll];
+        int wt[kMergeUnroll];
 #pragma unroll
         for (int u = 0; u < kMergeUnroll; ++u) {
             ck[u] = make_uint4(0, 0, 0, 0);
             cv[u] = make_uint4(0, 0, 0, 0);
+            wt[u] = 1;
             if (t + u <= hi) {
+                if (WEIGHTED) wt[u] = max(wrow[t + u], 1);
                 ck[u] = load_stream(src_k + (size_t)(t + u) * LPR);
                 cv[u] = load_stream(src_v + (size_t)(t + u) * LPR);
             }
@@ -79,16 +92,26 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
                 unpack<DT>(ck[u], xk);
                 unpack<DT>(cv[u], xv);
                 const bool first = (u == 0 && t == lo);  // the sum starts from the first row, so a bucket
-#pragma unroll                                           // of one is a bit-exact copy (-0 stays -0)
-                for (int e = 0; e < EPL; ++e) {
-                    acc_k[e] = first ? xk[e] : acc_k[e] + xk[e];
-                    acc_v[e] = first ? xv[e] : acc_v[e] + xv[e];
+                if (WEIGHTED) {                          // of one is a bit-exact copy (-0 stays -0)
+                    wsum += wt[u];
+                    const float w = use_w ? (float)wt[u] : 1.f;
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) {
+                        acc_k[e] = first ? w * xk[e] : fmaf(w, xk[e], acc_k[e]);
+                        acc_v[e] = first ? w * xv[e] : fmaf(w, xv[e], acc_v[e]);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) {
+                        acc_k[e] = first ? xk[e] : acc_k[e] + xk[e];
+                        acc_v[e] = first ? xv[e] : acc_v[e] + xv[e];
+                    }
                 }
             }
         }
     }
-    const int count = hi - lo + 1;
-    if (count > 1) {
+    const int count = WEIGHTED ? wsum : hi - lo + 1;
+    if (hi > lo) {
         const float cf = (float)count;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
@@ -101,10 +124,12 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
 
     // bookkeeping, once per score group: bucket size, position of the cache row, bucket of every position
     if (G == H || h == 0) {
-        const size_t bg = (size_t)b * G + (G == 1 ? 0 : h);
         if (sub == 0) {
             if (counts) counts[bg * n_anchor + j] = count;
-            if (pos) pos[bg * cap + j] = a[j];
+            if (pos) {
+                const int t = min(max(a[j], 0), T - 1);
+                pos[bg * cap + j] = src_pos ? src_pos[bg * T + t] : a[j];
+            }
         }
         if (assign)
             for (int t = blo + sub; t <= bhi; t += LPR) assign[bg * T + t] = (!evict_only || t == lo) ? j : -1;
@@ -112,27 +137,34 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
 }
 
 template <int DT, int D>
-static int launch_merge(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G,
-                        int T, int n_anchor, void* k_cache, void* v_cache, int cap, int32_t* counts, int32_t* assign,
-                        int32_t* pos, int evict_only, hipStream_t stream)
+static int launch_merge(const void* k, const void* v, const int32_t* anchor_idx, const int32_t* weights,
+                        const int32_t* src_pos, int B, int H, int G, int T, int src_rows, int n_anchor, void* k_cache,
+                        void* v_cache, int cap, int32_t* counts, int32_t* assign, int32_t* pos, int evict_only,
+                        hipStream_t stream)
 {
     constexpr int LPR = D * Elem<DT>::kBytes / 16;
     constexpr int GROUPS = kMergeThreads / LPR;
     dim3 grid((n_anchor + GROUPS - 1) / GROUPS, B * H);
-    hipLaunchKernelGGL((merge_compact_kernel<DT, D>), grid, dim3(kMergeThreads), 0, stream,
-                       (const uint4*)k, (const uint4*)v, anchor_idx, (uint4*)k_cache, (uint4*)v_cache,
-                       counts, assign, pos, H, G, T, n_anchor, cap, evict_only);
+    if (weights != nullptr && !evict_only)
+        hipLaunchKernelGGL((merge_compact_kernel<DT, D, true>), grid, dim3(kMergeThreads), 0, stream,
+                           (const uint4*)k, (const uint4*)v, anchor_idx, weights, src_pos, (uint4*)k_cache,
+                           (uint4*)v_cache, counts, assign, pos, H, G, T, src_rows, n_anchor, cap, evict_only);
+    else
+        hipLaunchKernelGGL((merge_compact_kernel<DT, D, false>), grid, dim3(kMergeThreads), 0, stream,
+                           (const uint4*)k, (const uint4*)v, anchor_idx, weights, src_pos, (uint4*)k_cache,
+                           (uint4*)v_cache, counts, assign, pos, H, G, T, src_rows, n_anchor, cap, evict_only);
     return status_from_hip(hipGetLastError());
 }
 
-int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G, int T,
-                   int D, int n_anchor, int dt, int evict_only, void* k_cache, void* v_cache, int cap,
-                   int32_t* counts, int32_t* assign, int32_t* pos, hipStream_t stream)
+int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, const int32_t* weights,
+                   const int32_t* src_pos, int B, int H, int G, int T, int src_rows, int D, int n_anchor, int dt,
+                   int evict_only, void* k_cache, void* v_cache, int cap, int32_t* counts, int32_t* assign,
+                   int32_t* pos, hipStream_t stream)
 {
-#define EC_MERGE_CASE(DT_, D_)                                                                      \
-    if (dt == DT_ && D == D_)                                                                       \
-        return launch_merge<DT_, D_>(k, v, anchor_idx, B, H, G, T, n_anchor, k_cache, v_cache, cap, counts, \
-                                     assign, pos, evict_only, stream);
+#define EC_MERGE_CASE(DT_, D_)                                                                               \
+    if (dt == DT_ && D == D_)                                                                                \
+        return launch_merge<DT_, D_>(k, v, anchor_idx, weights, src_pos, B, H, G, T, src_rows, n_anchor, k_cache, \
+                                     v_cache, cap, counts, assign, pos, evict_only, stream);
     EC_MERGE_CASE(EC_BF16, 128)
     EC_MERGE_CASE(EC_BF16, 64)
     EC_MERGE_CASE(EC_F32, 128)

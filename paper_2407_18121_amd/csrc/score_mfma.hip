@@ -1,4 +1,6 @@
-// ec_prefill_score, matrix-core path for bf16 inputs (Sec. 3.3, Eq. 1 and I_n = sum_m A_mn).
+// ec_prefill_score / ec_chunk_score, matrix-core path for bf16 inputs (Sec. 3.3, Eq. 1 and I_n = sum_m A_mn).
+// Geometry (ScoreGeom): Tq queries over L = P + Tq key rows, query m sees rows n <= P + m; the first-turn
+// prompt pass is P = 0.
 //
 // Three kernels, none of which stores the T x T matrix:
 //   vt_transpose : V [T,D] -> V^T [D,Tp] per head (zero-padded to a multiple of 64 keys), so that
@@ -51,12 +53,13 @@ __device__ __forceinline__ int xcd_contiguous_item(int linear_id, int total)
 
 // ------------------------------------------------------------------ V^T
 __global__ __launch_bounds__(256) void vt_transpose_kernel(const uint16_t* __restrict__ v,
-                                                           uint16_t* __restrict__ vt, int T, int Tp, int D)
+                                                           uint16_t* __restrict__ vt, int T, int Tp, int D,
+                                                           int kv_rows)
 {
     __shared__ uint16_t tile[64][64 + 2];
     const int bh = blockIdx.z;
     const int n0 = blockIdx.x * 64, d0 = blockIdx.y * 64;
-    const uint16_t* src = v + (size_t)bh * T * D;
+    const uint16_t* src = v + (size_t)bh * kv_rows * D;
     uint16_t* dst = vt + (size_t)bh * D * Tp;
     for (int i = threadIdx.x; i < 64 * 32; i += 256) {  // pairs of elements along d
         const int r = i / 32, c = (i % 32) * 2;
@@ -80,9 +83,10 @@ __global__ __launch_bounds__(256) void vt_transpose_kernel(const uint16_t* __res
 template <int D, int WAVES>
 __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
-    uint16_t* __restrict__ out, float* __restrict__ lse, int T, int Tp, float scale_log2e, int n_qtiles,
+    uint16_t* __restrict__ out, float* __restrict__ lse, ScoreGeom geo, int Tp, float scale_log2e, int n_qtiles,
     int n_heads)
 {
+    const int Tq = geo.Tq, P = geo.P, L = geo.L;
     constexpr int THREADS = WAVES * kWave;
     constexpr int BM = WAVES * 32;   // queries per workgroup
     constexpr int KB = D / 16;       // contraction blocks of Q.K
@@ -106,8 +110,8 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     const int m0 = (n_qtiles - 1 - item % n_qtiles) * BM;  // longest rows first inside a head
     const int mw = m0 + wave * 32;                          // first query of this wave
     const int m = mw + c32;                            // this lane's query
-    const uint16_t* qh = q + (size_t)bh * T * D;
-    const uint16_t* kh = k + (size_t)bh * T * D;
+    const uint16_t* qh = q + (size_t)bh * Tq * D;
+    const uint16_t* kh = k + (size_t)bh * geo.kv_rows * D;
     const uint16_t* vth = vt + (size_t)bh * D * Tp;
     const bool want_out = out != nullptr;
 
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) {
         uint4 x = make_uint4(0, 0, 0, 0);
-        if (m < T) x = *reinterpret_cast<const uint4*>(qh + (size_t)m * D + kb * 16 + h * 8);
+        if (m < Tq) x = *reinterpret_cast<const uint4*>(qh + (size_t)m * D + kb * 16 + h * 8);
         qf[kb] = __builtin_bit_cast(bf16x8, x);
     }
 
@@ -133,7 +137,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
             const int c = tid + i * THREADS;
             const int r = c / (D / 8), cc = c % (D / 8);
             kreg[i] = u32x4{0u, 0u, 0u, 0u};
-            if (n0 + r < T) kreg[i] = *reinterpret_cast<const u32x4*>(kh + (size_t)(n0 + r) * D + cc * 8);
+            if (n0 + r < L) kreg[i] = *reinterpret_cast<const u32x4*>(kh + (size_t)(n0 + r) * D + cc * 8);
         }
         if (want_out) {
 #pragma unroll
@@ -162,7 +166,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
         }
     };
 
-    const int n_end = min(T, m0 + BM);
+    const int n_end = min(L, P + m0 + BM);  // the workgroup's last query sees rows up to P + m0 + BM - 1
     fetch(0);
     stage(0);
     __syncthreads();
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
         const bool more = n0 + kFwdBN < n_end;
         if (more) fetch(n0 + kFwdBN);
 
-        if (n0 <= mw + 31) {  // otherwise every key of the tile is in this wave's future
+        if (n0 <= P + mw + 31) {  // otherwise every key of the tile is in this wave's future
             // S^T = K . Q^T : two 32-key blocks x this wave's 32 queries
             f32x16 s[2];
             {
@@ -201,13 +205,13 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
                 __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
             }
             // causal mask (diagonal tiles only), row max on the raw products
-            if ((n0 + kFwdBN - 1 > mw) || (n0 + kFwdBN > T)) {
+            if ((n0 + kFwdBN - 1 > P + mw) || (n0 + kFwdBN > L)) {
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int n = n0 + nb * 32 + (r / 8) * 16 + h * 8 + (r % 8);  // key of register r
-                        if (n > m || n >= T) s[nb][r] = -INFINITY;
+                        if (n > P + m || n >= L) s[nb][r] = -INFINITY;
                     }
             }
             float mx = -INFINITY;
@@ -270,11 +274,11 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
-    if (m < T) {
-        if (h == 0) lse[(size_t)bh * T + m] = (m_run + log2f(l_tot)) * kLn2;
+    if (m < Tq) {
+        if (h == 0) lse[(size_t)bh * Tq + m] = (m_run + log2f(l_tot)) * kLn2;
         if (want_out) {
             const float inv = 1.f / l_tot;
-            uint16_t* orow = out + ((size_t)bh * T + m) * D;
+            uint16_t* orow = out + ((size_t)bh * Tq + m) * D;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -292,10 +296,11 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 template <int D>
 __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const float* __restrict__ lse,
-    float* __restrict__ head_imp, int T, float scale_log2e, int n_ktiles, int n_heads)
+    float* __restrict__ head_imp, ScoreGeom geo, float scale_log2e, int n_ktiles, int n_heads)
 {
     constexpr int KB = D / 16;
     constexpr int QP = D + 8;
+    const int Tq = geo.Tq, P = geo.P, L = geo.L;
     __shared__ __align__(16) uint16_t qs[2][kColBM * QP];
     __shared__ __align__(16) float lse2[2][kColBM];  // row log-sum-exp in base-2 units
 
@@ -306,15 +311,15 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
     const int bh = item / n_ktiles;
     const int n0 = (item % n_ktiles) * kColBN;  // low key tiles (most query tiles) first inside a head
     const int n = n0 + wave * 32 + c32;  // this lane's key
-    const uint16_t* qh = q + (size_t)bh * T * D;
-    const uint16_t* kh = k + (size_t)bh * T * D;
-    const float* lh = lse + (size_t)bh * T;
+    const uint16_t* qh = q + (size_t)bh * Tq * D;
+    const uint16_t* kh = k + (size_t)bh * geo.kv_rows * D;
+    const float* lh = lse + (size_t)bh * Tq;
 
     bf16x8 kf[KB];
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) {
         uint4 x = make_uint4(0, 0, 0, 0);
-        if (n < T) x = *reinterpret_cast<const uint4*>(kh + (size_t)n * D + kb * 16 + h * 8);
+        if (n < L) x = *reinterpret_cast<const uint4*>(kh + (size_t)n * D + kb * 16 + h * 8);
         kf[kb] = __builtin_bit_cast(bf16x8, x);
     }
 
@@ -327,9 +332,9 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
             const int c = tid + i * kMfmaThreads;
             const int r = c / (D / 8), cc = c % (D / 8);
             qreg[i] = u32x4{0u, 0u, 0u, 0u};
-            if (m0 + r < T) qreg[i] = *reinterpret_cast<const u32x4*>(qh + (size_t)(m0 + r) * D + cc * 8);
+            if (m0 + r < Tq) qreg[i] = *reinterpret_cast<const u32x4*>(qh + (size_t)(m0 + r) * D + cc * 8);
         }
-        if (tid < kColBM) lreg = (m0 + tid < T) ? lh[m0 + tid] * kLog2e : INFINITY;
+        if (tid < kColBM) lreg = (m0 + tid < Tq) ? lh[m0 + tid] * kLog2e : INFINITY;
     };
     auto stage = [&](int buf) {
 #pragma unroll
@@ -342,16 +347,16 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
     };
 
     float col = 0.f;
-    const int m_begin = (n0 / kColBM) * kColBM;
+    const int m_begin = (max(n0 - P, 0) / kColBM) * kColBM;  // first query tile that sees key n0 (query m sees n <= P + m)
     fetch(m_begin);
     stage(0);
     __syncthreads();
     int buf = 0;
-    for (int m0 = m_begin; m0 < T; m0 += kColBM, buf ^= 1) {
-        const bool more = m0 + kColBM < T;
+    for (int m0 = m_begin; m0 < Tq; m0 += kColBM, buf ^= 1) {
+        const bool more = m0 + kColBM < Tq;
         if (more) fetch(m0 + kColBM);
 
-        if (m0 + kColBM - 1 >= n0 + wave * 32) {  // else every query of the tile precedes this wave's keys
+        if (P + m0 + kColBM - 1 >= n0 + wave * 32) {  // else no query of the tile sees this wave's keys
             constexpr int MB = kColBM / 32;  // 32-query blocks per tile
 #pragma unroll
             for (int mp = 0; mp < MB; mp += 2) {  // two blocks at a time: two independent MFMA chains
@@ -383,7 +388,7 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
                 // p = exp(s - lse_row), summed down the column.  Only blocks that touch the diagonal need
                 // the causal mask; the others take the three-instruction path (fma, exp, add).
                 const int mq = m0 + mp * 32;                     // first query of this pair of blocks
-                const bool diag = mq < n0 + wave * 32 + 31;      // some (query, key) pair has query < key
+                const bool diag = P + mq < n0 + wave * 32 + 31;  // some (query, key) pair is masked
                 if (diag) {
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb)
@@ -396,7 +401,7 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
                             for (int t = 0; t < 4; ++t) {
                                 const float p = __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + t], scale_log2e, -lr[t]));
                                 const int mm = mq + mb * 32 + g * 8 + h * 4 + t;
-                                col += (mm >= n) ? p : 0.f;  // rows beyond T carry lse = +inf, so p = 0
+                                col += (P + mm >= n) ? p : 0.f;  // rows beyond Tq carry lse = +inf, so p = 0
                             }
                         }
                 } else {
@@ -420,54 +425,56 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
         __syncthreads();
     }
     col += __shfl_xor(col, 32, kWave);
-    if (h == 0 && n < T) head_imp[(size_t)bh * T + n] = col;
+    if (h == 0 && n < L) head_imp[(size_t)bh * L + n] = col;
 }
 
 template <int D>
 static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse,
-                       float* head_imp, uint16_t* vt, int B, int H, int T, float scale, int forced_waves,
+                       float* head_imp, uint16_t* vt, int B, int H, ScoreGeom geo, float scale, int forced_waves,
                        hipStream_t stream)
 {
     const float sl = scale * kLog2e;
-    const int Tp = padded_T(T);
+    const int Tq = geo.Tq, L = geo.L;
+    const int Lp = padded_T(L);
     const int BH = B * H;
     if (out != nullptr) {
-        hipLaunchKernelGGL(vt_transpose_kernel, dim3(Tp / 64, D / 64, BH), dim3(256), 0, stream, v, vt, T, Tp, D);
+        hipLaunchKernelGGL(vt_transpose_kernel, dim3(Lp / 64, D / 64, BH), dim3(256), 0, stream, v, vt, L, Lp, D,
+                           geo.kv_rows);
         int rc = status_from_hip(hipGetLastError());
         if (rc != EC_OK) return rc;
     }
     // 8-wave workgroups (256 queries) halve the LDS staging per flop; 4-wave ones keep small prompts
     // spread over the chip
     int waves = forced_waves;
-    if (waves != 4 && waves != 8) waves = ((long long)BH * ((T + 255) / 256) >= 512) ? 8 : 4;
+    if (waves != 4 && waves != 8) waves = ((long long)BH * ((Tq + 255) / 256) >= 512) ? 8 : 4;
     if (waves == 8)
-        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 8>), dim3(xcd_grid(((T + 255) / 256) * BH)), dim3(512), 0,
-                           stream, q, k, vt, out, lse, T, Tp, sl, (T + 255) / 256, BH);
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 8>), dim3(xcd_grid(((Tq + 255) / 256) * BH)), dim3(512), 0,
+                           stream, q, k, vt, out, lse, geo, Lp, sl, (Tq + 255) / 256, BH);
     else
-        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 4>), dim3(xcd_grid(((T + 127) / 128) * BH)), dim3(256), 0,
-                           stream, q, k, vt, out, lse, T, Tp, sl, (T + 127) / 128, BH);
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 4>), dim3(xcd_grid(((Tq + 127) / 128) * BH)), dim3(256), 0,
+                           stream, q, k, vt, out, lse, geo, Lp, sl, (Tq + 127) / 128, BH);
     int rc = status_from_hip(hipGetLastError());
     if (rc != EC_OK) return rc;
-    hipLaunchKernelGGL((colsum_mfma_kernel<D>), dim3(xcd_grid(((T + kColBN - 1) / kColBN) * BH)),
-                       dim3(kMfmaThreads), 0, stream, q, k, lse, head_imp, T, sl, (T + kColBN - 1) / kColBN, BH);
+    hipLaunchKernelGGL((colsum_mfma_kernel<D>), dim3(xcd_grid(((L + kColBN - 1) / kColBN) * BH)),
+                       dim3(kMfmaThreads), 0, stream, q, k, lse, head_imp, geo, sl, (L + kColBN - 1) / kColBN, BH);
     return status_from_hip(hipGetLastError());
 }
 
-// bytes of workspace the V^T copy needs
+// bytes of workspace the V^T copy needs (T = number of key rows)
 size_t score_mfma_vt_bytes(int B, int H, int T, int D) { return (size_t)B * H * D * padded_T(T) * sizeof(uint16_t); }
 
-// Per-head importance into head_imp [B,H,T]; out may be NULL (then vt is not touched).
+// Per-head importance into head_imp [B,H,L]; out may be NULL (then vt is not touched).
 int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse, float* head_imp,
-                        void* vt, int B, int H, int T, int D, int dt, float scale, int forced_waves,
+                        void* vt, int B, int H, ScoreGeom geo, int D, int dt, float scale, int forced_waves,
                         hipStream_t stream)
 {
     if (dt != EC_BF16) return EC_EUNSUPPORTED;
     if (D == 128)
         return launch_mfma<128>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out, lse,
-                                head_imp, (uint16_t*)vt, B, H, T, scale, forced_waves, stream);
+                                head_imp, (uint16_t*)vt, B, H, geo, scale, forced_waves, stream);
     if (D == 64)
         return launch_mfma<64>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out, lse,
-                               head_imp, (uint16_t*)vt, B, H, T, scale, forced_waves, stream);
+                               head_imp, (uint16_t*)vt, B, H, geo, scale, forced_waves, stream);
     return EC_EUNSUPPORTED;
 }
 

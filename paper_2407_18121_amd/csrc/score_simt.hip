@@ -1,4 +1,5 @@
-// ec_prefill_score, vector-ALU path (fp32 arithmetic throughout).
+// ec_prefill_score / ec_chunk_score, vector-ALU path (fp32 arithmetic throughout).
+// Geometry (ScoreGeom): Tq queries over L = P + Tq key rows, query m sees rows n <= P + m.
 //
 // Used for fp32 inputs, where the contraction must be true fp32 (the matrix-core
 // bf16 path lives in score_mfma.hip), and as a fallback for shapes that path does
@@ -40,9 +41,9 @@ template <int DT> __device__ __forceinline__ void load4(const void* base, size_t
 }
 
 // s[i][j] = sum_d Q[m0 + ty*4 + i][d] * K[n0 + tx*2 + j][d]   (unscaled)
-// Rows/columns at or beyond T read as zero.
+// Query rows at or beyond Tq and key rows at or beyond L read as zero.
 template <int DT, int D>
-__device__ __forceinline__ void s_tile(const void* qh, const void* kh, int m0, int n0, int T,
+__device__ __forceinline__ void s_tile(const void* qh, const void* kh, int m0, int n0, int Tq, int L,
                                        SimtSmem& sm, float s[4][2])
 {
     const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
@@ -53,14 +54,14 @@ __device__ __forceinline__ void s_tile(const void* qh, const void* kh, int m0, i
         for (int u = tid; u < kBM * (kDC / 4); u += kSimtThreads) {
             const int r = u % kBM, c = u / kBM;
             float f[4] = {0.f, 0.f, 0.f, 0.f};
-            if (m0 + r < T) load4<DT>(qh, (size_t)(m0 + r) * D + d0 + c * 4, f);
+            if (m0 + r < Tq) load4<DT>(qh, (size_t)(m0 + r) * D + d0 + c * 4, f);
 #pragma unroll
             for (int i = 0; i < 4; ++i) sm.qt[c * 4 + i][r] = f[i];
         }
         for (int u = tid; u < kBN * (kDC / 4); u += kSimtThreads) {
             const int r = u % kBN, c = u / kBN;
             float f[4] = {0.f, 0.f, 0.f, 0.f};
-            if (n0 + r < T) load4<DT>(kh, (size_t)(n0 + r) * D + d0 + c * 4, f);
+            if (n0 + r < L) load4<DT>(kh, (size_t)(n0 + r) * D + d0 + c * 4, f);
 #pragma unroll
             for (int i = 0; i < 4; ++i) sm.kt[c * 4 + i][r] = f[i];
         }
@@ -89,9 +90,10 @@ __device__ __forceinline__ float row16_max(float x)
 template <int DT, int D>
 __global__ __launch_bounds__(kSimtThreads) void attn_fwd_simt_kernel(
     const void* __restrict__ q, const void* __restrict__ k, const void* __restrict__ v,
-    void* __restrict__ out, float* __restrict__ lse, int T, float scale_log2e)
+    void* __restrict__ out, float* __restrict__ lse, ScoreGeom geo, float scale_log2e)
 {
     constexpr int CPT = D / 16;  // output columns per thread
+    const int Tq = geo.Tq, P = geo.P, L = geo.L;
     __shared__ SimtSmem sm;
     __shared__ float ps[kBM][kBN + 1];
     __shared__ __align__(16) float vs[kBN][D];
@@ -100,9 +102,9 @@ __global__ __launch_bounds__(kSimtThreads) void attn_fwd_simt_kernel(
     const int bh = blockIdx.y;
     const int m0 = (gridDim.x - 1 - blockIdx.x) * kBM;  // longest rows first
     using E = typename Elem<DT>::type;
-    const E* qh = reinterpret_cast<const E*>(q) + (size_t)bh * T * D;
-    const E* kh = reinterpret_cast<const E*>(k) + (size_t)bh * T * D;
-    const E* vh = reinterpret_cast<const E*>(v) + (size_t)bh * T * D;
+    const E* qh = reinterpret_cast<const E*>(q) + (size_t)bh * Tq * D;
+    const E* kh = reinterpret_cast<const E*>(k) + (size_t)bh * geo.kv_rows * D;
+    const E* vh = reinterpret_cast<const E*>(v) + (size_t)bh * geo.kv_rows * D;
 
     float m_run[4], l_run[4], o[4][CPT];
 #pragma unroll
@@ -113,15 +115,15 @@ __global__ __launch_bounds__(kSimtThreads) void attn_fwd_simt_kernel(
         for (int c = 0; c < CPT; ++c) o[i][c] = 0.f;
     }
 
-    const int n_end = min(T, m0 + kBM);  // causal: keys up to the last query of the tile
+    const int n_end = min(L, P + m0 + kBM);  // causal: keys up to the last query of the tile
     for (int n0 = 0; n0 < n_end; n0 += kBN) {
         float s[4][2];
-        s_tile<DT, D>(qh, kh, m0, n0, T, sm, s);
-        // stage V tile (rows beyond T read as zero)
+        s_tile<DT, D>(qh, kh, m0, n0, Tq, L, sm, s);
+        // stage V tile (rows beyond L read as zero)
         for (int u = tid; u < kBN * (D / 4); u += kSimtThreads) {
             const int r = u / (D / 4), c = u % (D / 4);
             float f[4] = {0.f, 0.f, 0.f, 0.f};
-            if (n0 + r < T) load4<DT>(vh, (size_t)(n0 + r) * D + c * 4, f);
+            if (n0 + r < L) load4<DT>(vh, (size_t)(n0 + r) * D + c * 4, f);
             *reinterpret_cast<float4*>(&vs[r][c * 4]) = make_float4(f[0], f[1], f[2], f[3]);
         }
 #pragma unroll
@@ -131,7 +133,7 @@ __global__ __launch_bounds__(kSimtThreads) void attn_fwd_simt_kernel(
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int n = n0 + tx * 2 + j;
-                sv[j] = (n <= m && n < T) ? s[i][j] * scale_log2e : -INFINITY;
+                sv[j] = (n <= P + m && n < L) ? s[i][j] * scale_log2e : -INFINITY;
             }
             const float mt = row16_max(fmaxf(sv[0], sv[1]));
             const float m_new = fmaxf(m_run[i], mt);
@@ -172,11 +174,11 @@ __global__ __launch_bounds__(kSimtThreads) void attn_fwd_simt_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int m = m0 + ty * 4 + i;
-        if (m >= T) continue;
-        if (tx == 0) lse[(size_t)bh * T + m] = (m_run[i] + log2f(l_run[i])) * kLn2;
+        if (m >= Tq) continue;
+        if (tx == 0) lse[(size_t)bh * Tq + m] = (m_run[i] + log2f(l_run[i])) * kLn2;
         if (out != nullptr) {
             const float inv = 1.f / l_run[i];
-            E* orow = reinterpret_cast<E*>(out) + ((size_t)bh * T + m) * D + tx * CPT;
+            E* orow = reinterpret_cast<E*>(out) + ((size_t)bh * Tq + m) * D + tx * CPT;
 #pragma unroll
             for (int c = 0; c < CPT; ++c) {
                 const float r = o[i][c] * inv;
@@ -192,43 +194,44 @@ __global__ __launch_bounds__(kSimtThreads) void attn_fwd_simt_kernel(
 template <int DT, int D>
 __global__ __launch_bounds__(kSimtThreads) void colsum_simt_kernel(
     const void* __restrict__ q, const void* __restrict__ k, const float* __restrict__ lse,
-    float* __restrict__ head_imp, int T, float scale_log2e)
+    float* __restrict__ head_imp, ScoreGeom geo, float scale_log2e)
 {
     __shared__ SimtSmem sm;
     __shared__ float red[16][kBN];
+    const int Tq = geo.Tq, P = geo.P, L = geo.L;
 
     const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
     const int bh = blockIdx.y;
     const int n0 = blockIdx.x * kBN;  // low key tiles (most query tiles) are scheduled first
     using E = typename Elem<DT>::type;
-    const E* qh = reinterpret_cast<const E*>(q) + (size_t)bh * T * D;
-    const E* kh = reinterpret_cast<const E*>(k) + (size_t)bh * T * D;
-    const float* lh = lse + (size_t)bh * T;
+    const E* qh = reinterpret_cast<const E*>(q) + (size_t)bh * Tq * D;
+    const E* kh = reinterpret_cast<const E*>(k) + (size_t)bh * geo.kv_rows * D;
+    const float* lh = lse + (size_t)bh * Tq;
 
     float col[2] = {0.f, 0.f};
-    for (int m0 = (n0 / kBM) * kBM; m0 < T; m0 += kBM) {
+    for (int m0 = (max(n0 - P, 0) / kBM) * kBM; m0 < Tq; m0 += kBM) {  // query m sees keys n <= P + m
         float s[4][2];
-        s_tile<DT, D>(qh, kh, m0, n0, T, sm, s);
+        s_tile<DT, D>(qh, kh, m0, n0, Tq, L, sm, s);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int m = m0 + ty * 4 + i;
-            if (m >= T) continue;
+            if (m >= Tq) continue;
             const float l2 = lh[m] * kLog2e;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int n = n0 + tx * 2 + j;
-                if (n <= m) col[j] += exp2f(s[i][j] * scale_log2e - l2);
+                if (n <= P + m) col[j] += exp2f(s[i][j] * scale_log2e - l2);
             }
         }
     }
     red[ty][tx * 2] = col[0];
     red[ty][tx * 2 + 1] = col[1];
     __syncthreads();
-    if (tid < kBN && n0 + tid < T) {
+    if (tid < kBN && n0 + tid < L) {
         float acc = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc += red[r][tid];
-        head_imp[(size_t)bh * T + n0 + tid] = acc;
+        head_imp[(size_t)bh * L + n0 + tid] = acc;
     }
 }
 
@@ -261,28 +264,28 @@ int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, h
 
 template <int DT, int D>
 static int launch_simt(const void* q, const void* k, const void* v, void* out, float* lse,
-                       float* head_imp, int B, int H, int T, float scale, hipStream_t stream)
+                       float* head_imp, int B, int H, ScoreGeom geo, float scale, hipStream_t stream)
 {
     const float sl = scale * kLog2e;
-    dim3 g1((T + kBM - 1) / kBM, B * H);
+    dim3 g1((geo.Tq + kBM - 1) / kBM, B * H);
     hipLaunchKernelGGL((attn_fwd_simt_kernel<DT, D>), g1, dim3(kSimtThreads), 0, stream, q, k, v, out, lse,
-                       T, sl);
+                       geo, sl);
     int rc = status_from_hip(hipGetLastError());
     if (rc != EC_OK) return rc;
-    dim3 g2((T + kBN - 1) / kBN, B * H);
+    dim3 g2((geo.L + kBN - 1) / kBN, B * H);
     hipLaunchKernelGGL((colsum_simt_kernel<DT, D>), g2, dim3(kSimtThreads), 0, stream, q, k, lse, head_imp,
-                       T, sl);
+                       geo, sl);
     return status_from_hip(hipGetLastError());
 }
 
-// Per-head importance into head_imp [B,H,T]; out may be NULL.
+// Per-head importance into head_imp [B,H,L]; out may be NULL.
 int score_simt_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
-                        float* head_imp, int B, int H, int T, int D, int dt, float scale,
+                        float* head_imp, int B, int H, ScoreGeom geo, int D, int dt, float scale,
                         hipStream_t stream)
 {
 #define EC_SIMT_CASE(DT_, D_)                                                                     \
     if (dt == DT_ && D == D_)                                                                     \
-        return launch_simt<DT_, D_>(q, k, v, out, lse, head_imp, B, H, T, scale, stream);
+        return launch_simt<DT_, D_>(q, k, v, out, lse, head_imp, B, H, geo, scale, stream);
     EC_SIMT_CASE(EC_F32, 64)
     EC_SIMT_CASE(EC_F32, 128)
     EC_SIMT_CASE(EC_BF16, 64)

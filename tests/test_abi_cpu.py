@@ -49,6 +49,14 @@ def test_invalid_arguments_are_rejected_before_any_launch():
     assert lib.ec_prefill_score(one, one, one, None, None, one, 1, 1, 1, 8, 64, 0, 1.0, one, 16, None) == ec.EC_EWORKSPACE
     assert lib.ec_merge_compact(one, one, one, 1, 4, 2, 8, 64, 4, 0, 0, one, one, 4, None, None, None, None) == ec.EC_EINVAL  # G not in {1,H}
     assert lib.ec_merge_compact(one, one, one, 1, 4, 1, 8, 64, 4, 0, 7, one, one, 4, None, None, None, None) == ec.EC_EINVAL  # merge_mode
+    two = ctypes.c_void_p(512)
+    assert lib.ec_merge_compact(one, one, one, 1, 4, 1, 8, 64, 4, 0, 0, one, two, 4, None, None, None, None) == ec.EC_EINVAL  # in place
+    assert lib.ec_remerge_compact(one, one, 7, None, None, one, 1, 4, 1, 8, 64, 4, 0, 0, two, two, 4, None, None, None, None) == ec.EC_EINVAL  # src_rows < L
+    assert lib.ec_chunk_score(None, None, None, None, None, None, 1, 1, 1, 8, 4, 12, 64, 0, 1.0, None, 0, None) == ec.EC_EINVAL
+    assert lib.ec_chunk_score(one, one, one, None, None, one, 1, 1, 1, 8, 4, 11, 64, 0, 1.0, one, 1 << 20, None) == ec.EC_EINVAL  # kv_rows < P + T_new
+    assert lib.ec_chunk_score(one, one, one, None, None, one, 1, 1, 1, 0, 4, 12, 64, 0, 1.0, one, 1 << 20, None) == ec.EC_EINVAL  # empty chunk
+    assert lib.ec_chunk_score(one, one, one, None, None, one, 1, 1, 1, 8, -1, 12, 64, 0, 1.0, one, 1 << 20, None) == ec.EC_EINVAL  # negative prefix
+    assert lib.ec_chunk_score(one, one, one, None, None, one, 1, 1, 1, 8, 4, 12, 64, 0, 1.0, one, 16, None) == ec.EC_EWORKSPACE
 
 
 def test_evict_index_matches_oracle_everywhere():

@@ -1,0 +1,228 @@
+"""GPU parity: ec_chunk_score and ec_remerge_compact vs the CPU oracle -- a later multi-token pass over an
+existing compressed cache (Sec. 3.3: encoding covers chat history; Alg. 1's multi-token branch with a past)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2407_18121_amd import binding as ec
+from paper_2407_18121_amd import synthetic as syn
+from util import assert_close, quantize, to_dev, to_host, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+def _chunk_inputs(B, H, Tq, P, D, dtype, cid):
+    """Synthetic rows of a P+Tq token sequence: the first P stand for the cache, the rest are the chunk."""
+    cfg = syn.custom("t", H=H, D=D, B=B, T=P + Tq, dtype=dtype, cid=cid)
+    q, k, v = syn.prompt_qkv(cfg)
+    return np.ascontiguousarray(q[:, :, P:]), k, v, cfg.scale
+
+
+def _padded(x, extra, dtype):
+    """[B,H,L,D] -> device buffer [B,H,L+extra,D] whose spare rows are NaN (they must never be read)."""
+    B, H, L, D = x.shape
+    buf = torch.full((B, H, L + extra, D), float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    buf[:, :, :L] = to_dev(x, dtype)
+    return buf
+
+
+def run_gpu_chunk(q, k, v, P, extra, dtype, scale, G, want_out=True):
+    B, H, Tq, D = q.shape
+    L = P + Tq
+    dq, dk, dv = to_dev(q, dtype), _padded(k, extra, dtype), _padded(v, extra, dtype)
+    out = torch.full((B, H, Tq, D), float("nan"), dtype=torch_dtype(dtype), device="cuda") if want_out else None
+    lse = torch.full((B, H, Tq), float("nan"), dtype=torch.float32, device="cuda")
+    score = torch.full((B, G, L), float("nan"), dtype=torch.float32, device="cuda")
+    ws = ec.new_workspace(ec.EC_FN_PREFILL_SCORE, B, H, L, D, ec.dtype_code(dq))
+    ec.ec_chunk_score(dq, dk, dv, P, out, lse, score, scale, ws)
+    torch.cuda.synchronize()
+    return (None if out is None else to_host(out)), to_host(lse), to_host(score)
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+@pytest.mark.parametrize("B,H,Tq,P,extra,Gmode", [
+    (1, 2, 1, 37, 3, "layer"),      # one query: a generation step's attention
+    (2, 3, 37, 20, 0, "head"),
+    (1, 4, 200, 56, 10, "layer"),   # prefix not a multiple of any tile
+    (2, 2, 130, 321, 5, "layer"),   # prefix longer than the chunk
+    (1, 2, 64, 700, 0, "head"),
+    (1, 2, 300, 0, 7, "layer"),     # no prefix, strided source
+    (1, 2, 5, 1000, 0, "layer"),    # a few queries over a long cache
+    (1, 1, 257, 255, 1, "head"),
+])
+def test_chunk_score_parity(dtype, D, B, H, Tq, P, extra, Gmode):
+    q, k, v, scale = _chunk_inputs(B, H, Tq, P, D, dtype, 2000 + Tq + P)
+    G = 1 if Gmode == "layer" else H
+    ref = oracle.chunk_score(q, k, v, P, scale, G)
+    out, lse, score = run_gpu_chunk(q, k, v, P, extra, dtype, scale, G)
+    assert_close(out, ref["out"], dtype, "out")
+    assert_close(lse, ref["lse"], dtype, "lse")
+    assert_close(score, ref["score"], dtype, "score")
+    np.testing.assert_allclose(score.sum(-1), Tq, rtol=1e-5)   # every query row of A sums to one
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_chunk_score_without_prefix_is_prefill_score(dtype):
+    B, H, T, D = 2, 2, 333, 64
+    cfg = syn.custom("t", H=H, D=D, B=B, T=T, dtype=dtype, cid=77)
+    q, k, v = syn.prompt_qkv(cfg)
+    dq, dk, dv = to_dev(q, dtype), to_dev(k, dtype), to_dev(v, dtype)
+    outs = []
+    for chunk in (False, True):
+        out = torch.zeros((B, H, T, D), dtype=torch_dtype(dtype), device="cuda")
+        lse = torch.zeros((B, H, T), dtype=torch.float32, device="cuda")
+        score = torch.zeros((B, 1, T), dtype=torch.float32, device="cuda")
+        ws = ec.new_workspace(ec.EC_FN_PREFILL_SCORE, B, H, T, D, ec.dtype_code(dq))
+        if chunk:
+            ec.ec_chunk_score(dq, dk, dv, 0, out, lse, score, cfg.scale, ws)
+        else:
+            ec.ec_prefill_score(dq, dk, dv, out, lse, score, cfg.scale, ws)
+        torch.cuda.synchronize()
+        outs.append((out, lse, score))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_chunk_score_output_not_wanted():
+    q, k, v, scale = _chunk_inputs(1, 2, 90, 140, 128, "bf16", 55)
+    ref = oracle.chunk_score(q, k, v, 140, scale, 1, want_out=False)
+    out, lse, score = run_gpu_chunk(q, k, v, 140, 2, "bf16", scale, 1, want_out=False)
+    assert out is None
+    assert_close(score, ref["score"], "bf16", "score")
+    assert_close(lse, ref["lse"], "bf16", "lse")
+
+
+def _anchors(rng, B, G, T, n):
+    return np.stack([np.stack([np.sort(rng.choice(T, n, replace=False)) for _ in range(G)])
+                     for _ in range(B)]).astype(np.int32)
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+@pytest.mark.parametrize("B,H,Gmode,L,n,extra,weighted", [
+    (1, 2, "layer", 9, 3, 2, True), (2, 3, "head", 100, 17, 0, True), (1, 4, "layer", 256, 128, 30, True),
+    (2, 2, "head", 1000, 100, 7, True), (1, 2, "layer", 1030, 515, 1, False), (1, 1, "layer", 700, 1, 0, True),
+])
+def test_remerge_compact_parity(dtype, D, B, H, Gmode, L, n, extra, weighted):
+    rng = np.random.default_rng(L * 17 + n + D)
+    G = 1 if Gmode == "layer" else H
+    k = quantize(rng.standard_normal((B, H, L, D)) * 2, dtype)
+    v = quantize(rng.standard_normal((B, H, L, D)), dtype)
+    a = _anchors(rng, B, G, L, n)
+    w = rng.integers(1, 40, (B, G, L)).astype(np.int32)          # tokens each source row already stands for
+    src_pos = np.cumsum(w, axis=-1).astype(np.int32) - 1          # any increasing map row -> original position
+    assign, counts = oracle.assign_nearest(a, L)
+    if weighted:
+        ok, wsum = oracle.merge_weighted(k, assign, w, n)
+        ov, _ = oracle.merge_weighted(v, assign, w, n)
+    else:
+        ok, ov, wsum = oracle.merge_compact(k, assign, n), oracle.merge_compact(v, assign, n), counts
+    cap = n + 3
+    dk_c = torch.full((B, H, cap, D), 9.0, dtype=torch_dtype(dtype), device="cuda")
+    dv_c = torch.full((B, H, cap, D), 9.0, dtype=torch_dtype(dtype), device="cuda")
+    d_counts = torch.full((B, G, n), -1, dtype=torch.int32, device="cuda")
+    d_assign = torch.full((B, G, L), -1, dtype=torch.int32, device="cuda")
+    d_pos = torch.full((B, G, cap), -5, dtype=torch.int32, device="cuda")
+    ec.ec_remerge_compact(_padded(k, extra, dtype), _padded(v, extra, dtype), L, torch.from_numpy(a).cuda(), dk_c, dv_c,
+                          weights=torch.from_numpy(w).cuda() if weighted else None,
+                          src_pos=torch.from_numpy(src_pos).cuda(), counts=d_counts, assign=d_assign, pos=d_pos)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(d_counts.cpu().numpy(), wsum)
+    np.testing.assert_array_equal(d_assign.cpu().numpy(), assign)
+    np.testing.assert_array_equal(d_pos.cpu().numpy()[:, :, :n], np.take_along_axis(src_pos, a, axis=-1))
+    assert (d_pos.cpu().numpy()[:, :, n:] == -5).all()
+    assert_close(to_host(dk_c)[:, :, :n], ok, dtype, "k_cache", stored=True)
+    assert_close(to_host(dv_c)[:, :, :n], ov, dtype, "v_cache", stored=True)
+    assert (to_host(dk_c)[:, :, n:] == 9.0).all() and (to_host(dv_c)[:, :, n:] == 9.0).all()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_remerge_unit_weights_and_single_rows_are_bit_exact(dtype):
+    B, H, L, D, n = 2, 2, 400, 128, 90
+    rng = np.random.default_rng(3)
+    k, v = quantize(rng.standard_normal((B, H, L, D)) * 3, dtype), quantize(rng.standard_normal((B, H, L, D)), dtype)
+    k[:, :, ::5, ::3] = -0.0
+    a = _anchors(rng, B, 1, L, n)
+    a[:, :, :30] = np.arange(30)           # the first buckets hold a single row each
+    a = np.sort(a, axis=-1)
+    a[:, :, 30:] = np.maximum(a[:, :, 30:], np.arange(30, n) * 4)   # keep them strictly ascending
+    for b in range(B):
+        assert (np.diff(a[b, 0]) > 0).all()
+    dk, dv, da = to_dev(k, dtype), to_dev(v, dtype), torch.from_numpy(a).cuda()
+    plain_k = torch.zeros((B, H, n, D), dtype=torch_dtype(dtype), device="cuda"); plain_v = torch.zeros_like(plain_k)
+    ones_k = torch.zeros_like(plain_k); ones_v = torch.zeros_like(plain_k)
+    big_k = torch.zeros_like(plain_k); big_v = torch.zeros_like(plain_k)
+    ec.ec_merge_compact(dk, dv, da, plain_k, plain_v)
+    ec.ec_remerge_compact(dk, dv, L, da, ones_k, ones_v, weights=torch.ones((B, 1, L), dtype=torch.int32, device="cuda"))
+    ec.ec_remerge_compact(dk, dv, L, da, big_k, big_v, weights=torch.full((B, 1, L), 1000003, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    it = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(plain_k.view(it), ones_k.view(it)) and torch.equal(plain_v.view(it), ones_v.view(it))
+    # a bucket of one row is a copy whatever weight the row carries
+    assert torch.equal(big_k[:, :, :29].view(it), dk[:, :, :29].view(it))
+    assert torch.equal(big_v[:, :, :29].view(it), dv[:, :, :29].view(it))
+
+
+def test_second_turn_stages_against_the_oracle():
+    """Turn 1 compresses a prompt; a few tokens are generated; turn 2 appends a chunk behind the cache rows
+    and compresses [cache | chunk] again.  Every GPU stage is fed the oracle's upstream result."""
+    dtype, B, H, D, T1, T2, steps = "bf16", 2, 4, 128, 300, 170, 6
+    cfg = syn.custom("t", H=H, D=D, B=B, T=T1, dtype=dtype, cid=901, gamma=(1, 4), decode_steps=steps)
+    q1, k1, v1 = syn.prompt_qkv(cfg)
+    n1 = -(-T1 // 4)
+    s1 = oracle.prefill_score(q1, k1, v1, cfg.scale, 1)["score"].astype(np.float32)
+    a1 = oracle.select_anchors(s1, n1, 1, 1)
+    assign1, counts1 = oracle.assign_nearest(a1, T1)
+    cap = n1 + steps + T2 + 4
+    kc = quantize(oracle.merge_compact(k1, assign1, n1, cap), dtype).astype(np.float64)
+    vc = quantize(oracle.merge_compact(v1, assign1, n1, cap), dtype).astype(np.float64)
+    pos = np.zeros((B, 1, cap), np.int32); pos[:, :, :n1] = a1
+    w = np.zeros((B, 1, cap), np.int32); w[:, :, :n1] = counts1
+    # generated tokens are appended without eviction here; they weigh 1
+    qd, kd, vd = syn.decode_stream(cfg, 0)
+    for s in range(steps):
+        oracle.decode_step(qd[s], kd[s], vd[s], kc, vc, pos, n1 + s, -1, T1 + s, cfg.scale)
+        w[:, :, n1 + s] = 1
+    P = n1 + steps
+    # the second turn's chunk
+    cfg2 = syn.custom("t2", H=H, D=D, B=B, T=T2, dtype=dtype, cid=902)
+    q2, k2, v2 = syn.prompt_qkv(cfg2)
+    kc[:, :, P:P + T2] = k2; vc[:, :, P:P + T2] = v2
+    pos[:, :, P:P + T2] = T1 + steps + np.arange(T2); w[:, :, P:P + T2] = 1
+    L = P + T2
+    ref = oracle.chunk_score(q2, kc[:, :, :L], vc[:, :, :L], P, cfg.scale, 1)
+    n2 = -(-(T1 + steps + T2) // 4)
+    s2 = ref["score"].astype(np.float32)
+    a2 = oracle.select_anchors(s2, n2, 1, 1)
+    assign2, _ = oracle.assign_nearest(a2, L)
+    ok, wsum = oracle.merge_weighted(kc[:, :, :L], assign2, w[:, :, :L], n2)
+    ov, _ = oracle.merge_weighted(vc[:, :, :L], assign2, w[:, :, :L], n2)
+    okp = oracle.merge_compact(kc[:, :, :L], assign2, n2)
+
+    dkc, dvc = to_dev(kc, dtype), to_dev(vc, dtype)
+    out = torch.zeros((B, H, T2, D), dtype=torch.bfloat16, device="cuda")
+    score = torch.zeros((B, 1, L), dtype=torch.float32, device="cuda")
+    ws = ec.new_workspace(ec.EC_FN_PREFILL_SCORE, B, H, L, D, ec.EC_BF16)
+    ec.ec_chunk_score(to_dev(q2, dtype), dkc, dvc, P, out, None, score, cfg.scale, ws)
+    torch.cuda.synchronize()
+    assert_close(to_host(out), ref["out"], dtype, "turn-2 out")
+    assert_close(to_host(score), ref["score"], dtype, "turn-2 score")
+    idx = torch.zeros((B, 1, n2), dtype=torch.int32, device="cuda")
+    ec.ec_select_anchors(torch.from_numpy(s2).cuda(), n2, 1, 1, idx)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(idx.cpu().numpy(), a2)
+    nk, nv = torch.zeros((B, H, cap, D), dtype=torch.bfloat16, device="cuda"), torch.zeros((B, H, cap, D), dtype=torch.bfloat16, device="cuda")
+    ncount = torch.zeros((B, 1, n2), dtype=torch.int32, device="cuda")
+    npos = torch.zeros((B, 1, cap), dtype=torch.int32, device="cuda")
+    ec.ec_remerge_compact(dkc, dvc, L, torch.from_numpy(a2).cuda(), nk, nv, weights=torch.from_numpy(np.ascontiguousarray(w[:, :, :L])).cuda(),
+                          src_pos=torch.from_numpy(np.ascontiguousarray(pos[:, :, :L])).cuda(), counts=ncount, pos=npos)
+    torch.cuda.synchronize()
+    assert_close(to_host(nk)[:, :, :n2], ok, dtype, "turn-2 k_cache", stored=True)
+    assert_close(to_host(nv)[:, :, :n2], ov, dtype, "turn-2 v_cache", stored=True)
+    np.testing.assert_array_equal(ncount.cpu().numpy(), wsum)
+    assert int(ncount.sum()) == B * (T1 + steps + T2)            # every original token is accounted for
+    np.testing.assert_array_equal(npos.cpu().numpy()[:, :, :n2], np.take_along_axis(pos[:, :, :L], a2, axis=-1))
+    # Alg. 1's plain mean over the same rows
+    ec.ec_remerge_compact(dkc, dvc, L, torch.from_numpy(a2).cuda(), nk, nv)
+    torch.cuda.synchronize()
+    assert_close(to_host(nk)[:, :, :n2], okp, dtype, "turn-2 k_cache (plain mean)", stored=True)
