@@ -7,8 +7,12 @@ for every layer ec_prefill_score -> ec_select_anchors -> ec_merge_compact, then
 (host) -> ec_decode_step on that layer's own compressed cache.  All inputs are
 resident in HBM before the timed region.  Prints ONE JSON line.
 
+After the timed region it also times, outside `value`, a second turn (`detail.turn2`): a new chunk of
+`--turn2` tokens (default: half the prompt) is encoded over the cache the generation left behind with
+ec_chunk_score -> ec_select_anchors -> ec_remerge_compact.
+
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--score-mode layer|head]
-                    [--no-graph] [--no-cpu-baseline]
+                    [--no-graph] [--no-cpu-baseline] [--turn2 N]
 """
 from __future__ import annotations
 
@@ -42,6 +46,8 @@ def parse():
                     help="profiling aid: run only the first N generated tokens (the JSON line says so)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (reference dispatch for HBM counters)")
+    ap.add_argument("--turn2", type=int, default=-1,
+                    help="tokens of the second-turn chunk timed after the main step (-1 = half the prompt, 0 = skip)")
     ap.add_argument("--distinct-layers", type=int, default=0,
                     help="distinct prompt tensors to generate (0 = one per layer; fewer are cycled)")
     return ap.parse_args()
@@ -146,6 +152,75 @@ class Workload:
         f = self.lib.ec_decode_step
         for a in self.decode_calls:
             rc = f(*a, s)
+            assert rc == 0, rc
+
+
+class Turn2:
+    """A second turn over the cache the generation left: chunk scoring, anchor selection, re-merge (all layers)."""
+
+    def __init__(self, wl, T_new):
+        import torch
+        from paper_2407_18121_amd import synthetic as syn
+        from paper_2407_18121_amd import synthetic_torch as synt
+        cfg, ec = wl.cfg, wl.ec
+        self.wl, self.lib = wl, wl.lib
+        B, H, D, L, G = cfg.B, cfg.H, cfg.D, cfg.layers, wl.G
+        dt = synt.torch_dtype(cfg)
+        self.P, self.Tq = wl.final_len, T_new
+        self.Lr = Lr = self.P + T_new
+        n_seen = cfg.T + cfg.decode_steps + T_new
+        self.n2 = n2 = min(Lr, -(-cfg.gamma[0] * n_seen // cfg.gamma[1]))
+        n_src = min(L, 4)   # distinct source buffers, cycled over the layers
+        chunk_cfg = syn.custom(cfg.name + "-turn2", H=H, D=D, B=B, T=T_new, dtype=cfg.dtype, cid=cfg.cid + 500)
+        self.q, self.k, self.v = [], [], []
+        for i in range(n_src):
+            q, k, v = synt.prompt_qkv_device(chunk_cfg, i)
+            kb = torch.zeros((B, H, Lr, D), dtype=dt, device="cuda")
+            vb = torch.zeros((B, H, Lr, D), dtype=dt, device="cuda")
+            kb[:, :, :self.P] = wl.k_cache[i][:, :, :self.P]
+            vb[:, :, :self.P] = wl.v_cache[i][:, :, :self.P]
+            kb[:, :, self.P:] = k
+            vb[:, :, self.P:] = v
+            self.q.append(q); self.k.append(kb); self.v.append(vb)
+        self.out = torch.empty((B, H, T_new, D), dtype=dt, device="cuda")
+        self.score = torch.empty((B, G, Lr), dtype=torch.float32, device="cuda")
+        self.anchor = torch.empty((B, G, n2), dtype=torch.int32, device="cuda")
+        self.counts = torch.empty((B, G, n2), dtype=torch.int32, device="cuda")
+        self.nk = torch.empty((B, H, n2, D), dtype=dt, device="cuda")
+        self.nv = torch.empty((B, H, n2, D), dtype=dt, device="cuda")
+        self.ws = ec.new_workspace(ec.EC_FN_PREFILL_SCORE, B, H, Lr, D, wl.dt_code)
+        ws, wsb = self.ws.data_ptr(), self.ws.numel()
+        self.score_calls, self.select_calls, self.merge_calls = [], [], []
+        for l in range(L):
+            i = l % n_src
+            self.score_calls.append((self.q[i].data_ptr(), self.k[i].data_ptr(), self.v[i].data_ptr(), self.out.data_ptr(),
+                                     None, self.score.data_ptr(), B, H, G, T_new, self.P, Lr, D, wl.dt_code, cfg.scale, ws, wsb))
+            self.select_calls.append((self.score.data_ptr(), B, G, Lr, n2, 1, 1, self.anchor.data_ptr(), None, 0))
+            self.merge_calls.append((self.k[i].data_ptr(), self.v[i].data_ptr(), Lr, None, None, self.anchor.data_ptr(), B, H, G,
+                                     Lr, D, n2, wl.dt_code, 0, self.nk.data_ptr(), self.nv.data_ptr(), n2,
+                                     self.counts.data_ptr(), None, None))
+        pairs = float(T_new) * self.P + T_new * (T_new + 1) / 2.0   # visible (query, key) pairs per head
+        self.score_flops_per_layer = 6.0 * D * pairs * B * H
+        self.merge_bytes_per_layer = 2.0 * B * H * D * cfg.esize * (Lr + n2)
+
+    def run_score(self, s):
+        for a in self.score_calls:
+            rc = self.lib.ec_chunk_score(*a, s)
+            assert rc == 0, rc
+
+    def run_select(self, s):
+        for a in self.select_calls:
+            rc = self.lib.ec_select_anchors(*a, s)
+            assert rc == 0, rc
+
+    def run_merge(self, s):
+        for a in self.merge_calls:
+            rc = self.lib.ec_remerge_compact(*a, s)
+            assert rc == 0, rc
+
+    def run_all(self, s):
+        for a, b, c in zip(self.score_calls, self.select_calls, self.merge_calls):
+            rc = self.lib.ec_chunk_score(*a, s) | self.lib.ec_select_anchors(*b, s) | self.lib.ec_remerge_compact(*c, s)
             assert rc == 0, rc
 
 
@@ -306,6 +381,29 @@ def main():
     do_prefill()  # restore the compressed caches for whoever looks at them next
     torch.cuda.synchronize()
 
+    turn2 = None
+    t2_len = cfg.T // 2 if args.turn2 < 0 else args.turn2
+    if t2_len > 0:
+        print(f"[bench] second turn: chunk of {t2_len} tokens over the generated cache", file=sys.stderr, flush=True)
+        do_decode()   # leaves every layer's cache as the generation ends
+        torch.cuda.synchronize()
+        t2 = Turn2(wl, t2_len)
+        t2.run_all(wl._stream())   # eager validation pass
+        torch.cuda.synchronize()
+        def t2_ms(run):
+            fn = (capture(torch, run) if use_graph else None) or (lambda: run(wl._stream()))
+            fn()
+            return timed(torch, fn, 3) / L
+        a_ms, s_ms, sel_ms, m_ms = t2_ms(t2.run_all), t2_ms(t2.run_score), t2_ms(t2.run_select), t2_ms(t2.run_merge)
+        t2_tflops = t2.score_flops_per_layer / (s_ms * 1e-3) / 1e12
+        turn2 = {"chunk_tokens": t2_len, "cache_rows_before": t2.P, "cache_rows_after": t2.n2,
+                 "us_per_layer": a_ms * 1e3, "score_us_per_layer": s_ms * 1e3, "select_us_per_layer": sel_ms * 1e3,
+                 "merge_us_per_layer": m_ms * 1e3, "score_TFLOPs": t2_tflops,
+                 "merge_GBps": t2.merge_bytes_per_layer / (m_ms * 1e-3) / 1e9}
+        del t2
+        do_prefill()
+        torch.cuda.synchronize()
+
     n_dec = len(wl.decode_calls)
     dec_launch_us = decode_ms * 1e3 / n_dec
     dec_gbps = wl.decode_bytes / (decode_ms * 1e-3) / 1e9
@@ -346,6 +444,8 @@ def main():
             "traffic": None,
         },
     }
+    if turn2 is not None:
+        res["detail"]["turn2"] = turn2
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         res["cpu_baseline"] = cpu_baseline(cfg, wl, wl.G)

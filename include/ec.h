@@ -180,7 +180,8 @@ int ec_merge_compact(const void* k, const void* v, const int32_t* anchor_idx, in
  *              the mean of the original tokens, and counts[j] = sum w_t.  Ignored by EC_MERGE_EVICT.
  *   src_pos    DEVICE [B,G,L] int32 or NULL: original position of every source row; pos[j] is then
  *              src_pos[anchor_j] instead of anchor_j
- * k_cache / v_cache must not be k / v (rows are written while others are still being read).
+ * k_cache / v_cache must not be k / v, and pos must not overlap src_pos (rows are written while others
+ * are still being read).
  * Everything else is as in ec_merge_compact, which is this call with src_rows = T and both NULL.
  */
 int ec_remerge_compact(const void* k, const void* v, int src_rows, const int32_t* weights,

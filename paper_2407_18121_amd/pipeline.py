@@ -2,6 +2,8 @@
 
 prefill():  ec_prefill_score -> ec_select_anchors -> ec_merge_compact      (Sec. 3.3 Instruction Encoding)
 decode():   ec_evict_index (host) -> ec_decode_step                        (Sec. 3.3 Output Generation)
+extend():   ec_chunk_score -> ec_select_anchors -> ec_remerge_compact      (a later turn: chat history is
+                                                                            compressed again with the new chunk)
 """
 from __future__ import annotations
 
@@ -44,3 +46,31 @@ class LayerState:
         if idx < 0:
             self.cache_len += 1
         return idx
+
+    def extend(self, q, k, v, scale, ws_chunk, out=None, lse=None):
+        """A later multi-token pass: the chunk's K/V rows go behind the cache rows, the chunk's queries score
+        every row of [cache | chunk], and the rows are merged again (Alg. 1's plain mean) into
+        ceil(gamma * tokens seen) rows."""
+        T_new = q.shape[2]
+        P, L = self.cache_len, self.cache_len + T_new
+        if L > self.cap:
+            raise ValueError(f"cache capacity {self.cap} cannot hold {P} rows + a chunk of {T_new}")
+        self.k_cache[:, :, P:L].copy_(k)
+        self.v_cache[:, :, P:L].copy_(v)
+        self.pos[:, :, P:L] = torch.arange(self.n_seen, self.n_seen + T_new, dtype=torch.int32, device=self.pos.device)
+        self.n_seen += T_new
+        n_new = -(-self.gamma[0] * self.n_seen // self.gamma[1])
+        n_new = max(min(n_new, L), self.protect_first + self.protect_last)
+        dev = self.k_cache.device
+        self.score = torch.empty((self.B, self.G, L), dtype=torch.float32, device=dev)
+        ec.ec_chunk_score(q, self.k_cache, self.v_cache, P, out, lse, self.score, scale, ws_chunk)
+        self.anchor_idx = torch.empty((self.B, self.G, n_new), dtype=torch.int32, device=dev)
+        ec.ec_select_anchors(self.score, n_new, self.protect_first, self.protect_last, self.anchor_idx)
+        src_pos = self.pos[:, :, :L].clone()  # the merge writes self.pos while it reads the old map
+        k_next, v_next = torch.zeros_like(self.k_cache), torch.zeros_like(self.v_cache)
+        self.counts = torch.empty((self.B, self.G, n_new), dtype=torch.int32, device=dev)
+        ec.ec_remerge_compact(self.k_cache, self.v_cache, L, self.anchor_idx, k_next, v_next, src_pos=src_pos,
+                              counts=self.counts, pos=self.pos)
+        self.k_cache, self.v_cache = k_next, v_next
+        self.n_anchor = self.cache_len = n_new
+        return n_new

@@ -226,3 +226,44 @@ def test_second_turn_stages_against_the_oracle():
     ec.ec_remerge_compact(dkc, dvc, L, torch.from_numpy(a2).cuda(), nk, nv)
     torch.cuda.synchronize()
     assert_close(to_host(nk)[:, :, :n2], okp, dtype, "turn-2 k_cache (plain mean)", stored=True)
+
+
+def test_layer_state_second_turn_calls_the_same_entry_points():
+    """pipeline.LayerState.extend is marshalling only: its result equals the three calls made by hand."""
+    from paper_2407_18121_amd.pipeline import LayerState
+    dtype, B, H, D, T1, T2 = "bf16", 1, 4, 128, 260, 120
+    cfg = syn.custom("t", H=H, D=D, B=B, T=T1, dtype=dtype, cid=903, gamma=(1, 4), decode_steps=40)
+    cfg2 = syn.custom("t2", H=H, D=D, B=B, T=T2, dtype=dtype, cid=904)
+    q1, k1, v1 = (to_dev(x, dtype) for x in syn.prompt_qkv(cfg))
+    q2, k2, v2 = (to_dev(x, dtype) for x in syn.prompt_qkv(cfg2))
+    n1 = -(-T1 // 4)
+    cap = n1 + 40 + T2
+    st = LayerState(B, H, D, T1, n1, cap, torch.bfloat16, (1, 4))
+    ws = ec.new_workspace(ec.EC_FN_PREFILL_SCORE, B, H, max(T1, cap), D, ec.EC_BF16)
+    st.prefill(q1, k1, v1, cfg.scale, ws)
+    d_out = torch.empty((B, H, D), dtype=torch.bfloat16, device="cuda")
+    qd, kd, vd = syn.decode_stream(cfg, 0)
+    for s in range(40):      # long enough for the fixed-point elimination to start removing rows
+        st.decode(to_dev(qd[s], dtype), to_dev(kd[s], dtype), to_dev(vd[s], dtype), cfg.scale, d_out, None)
+    P = st.cache_len
+    assert P < n1 + 40
+    kc, vc, pos = st.k_cache.clone(), st.v_cache.clone(), st.pos.clone()
+    n2 = st.extend(q2, k2, v2, cfg.scale, ws)
+    torch.cuda.synchronize()
+    L = P + T2
+    assert n2 == -(-(T1 + 40 + T2) // 4) and st.cache_len == n2 and st.n_seen == T1 + 40 + T2
+    kc[:, :, P:L] = k2; vc[:, :, P:L] = v2
+    pos[:, :, P:L] = torch.arange(T1 + 40, T1 + 40 + T2, dtype=torch.int32, device="cuda")
+    score = torch.empty((B, 1, L), dtype=torch.float32, device="cuda")
+    ec.ec_chunk_score(q2, kc, vc, P, None, None, score, cfg.scale, ws)
+    idx = torch.empty((B, 1, n2), dtype=torch.int32, device="cuda")
+    ec.ec_select_anchors(score, n2, 1, 1, idx)
+    nk, nv = torch.zeros_like(kc), torch.zeros_like(vc)
+    npos = pos.clone()
+    ec.ec_remerge_compact(kc, vc, L, idx, nk, nv, src_pos=pos[:, :, :L].clone(), pos=npos)
+    torch.cuda.synchronize()
+    assert torch.equal(score, st.score) and torch.equal(idx, st.anchor_idx)
+    assert torch.equal(nk[:, :, :n2], st.k_cache[:, :, :n2]) and torch.equal(nv[:, :, :n2], st.v_cache[:, :, :n2])
+    assert torch.equal(npos[:, :, :n2], st.pos[:, :, :n2])
+    p = st.pos[0, 0, :n2].cpu().numpy()
+    assert (np.diff(p) > 0).all() and p[0] == 0 and p[-1] == T1 + 40 + T2 - 1   # original positions stay ordered

@@ -26,6 +26,29 @@ def _host(t):
     return t.float().cpu().numpy()
 
 
+def _assert_valid_selection(score, anchors, pf=1, pl=1):
+    """The anchors are the protected ends plus the highest scores, equal scores going to the lower position
+    (checked from the definition, on whatever fp32 scores the selection was given)."""
+    B, G, T = score.shape
+    for b in range(B):
+        for g in range(G):
+            s, a = score[b, g], anchors[b, g]
+            sel = np.zeros(T, bool)
+            sel[a] = True
+            assert sel.sum() == a.size and sel[:pf].all() and sel[T - pl:].all()
+            free = np.ones(T, bool)
+            free[:pf] = False
+            free[T - pl:] = False
+            chosen, rest = free & sel, free & ~sel
+            if not chosen.any() or not rest.any():
+                continue
+            thr = s[chosen].min()
+            assert s[rest].max() <= thr
+            tie_sel, tie_rest = np.flatnonzero(chosen & (s == thr)), np.flatnonzero(rest & (s == thr))
+            if tie_rest.size:
+                assert tie_sel.max() < tie_rest.min()
+
+
 @pytest.mark.parametrize("name", ALL)
 def test_prefill_chain_full_shape(name):
     cfg = syn.CONFIGS[name]
@@ -81,7 +104,7 @@ def test_prefill_chain_full_shape(name):
     torch.cuda.synchronize()
     a = anchors.cpu().numpy()
     assert (np.diff(a, axis=-1) > 0).all() and (a[..., 0] == 0).all() and (a[..., -1] == T - 1).all()
-    np.testing.assert_array_equal(a, oracle.select_anchors(sc, nA, 1, 1))   # same fp32 scores on both sides
+    _assert_valid_selection(sc, a)
     cn = counts.cpu().numpy()
     assert (cn.sum(-1) == T).all() and (cn >= 1).all()                        # merged count weights are conserved
     # first moment per head: sum_k count_k * KV_k = sum_t kv_t, up to the bf16 rounding of the stored rows
@@ -137,3 +160,77 @@ def test_select_head_wise_full_shape():
     ec.ec_select_anchors(score, cfg.n_anchor, 1, 1, idx)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(idx.cpu().numpy(), oracle.select_anchors(score.cpu().numpy(), cfg.n_anchor, 1, 1))
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C5", "T4"])
+def test_second_turn_full_shape(name):
+    """A later chunk over the cache a finished generation leaves (multi-turn chat; Alg. 1's multi-token
+    branch with a past), at the workload's shape: chunk scoring, selection and weighted re-merge."""
+    cfg = syn.CONFIGS[name]
+    B, H, D = cfg.B, cfg.H, cfg.D
+    dt = synt.torch_dtype(cfg)
+    p, qd = cfg.gamma
+    P = cfg.n_anchor
+    for step in range(cfg.decode_steps):
+        P += 0 if ec.ec_evict_index(cfg.T + step + 1, P + 1, p, qd) >= 0 else 1
+    Tq = min(cfg.T // 2, 2048)
+    L, rows = P + Tq, P + Tq + 5
+    n2 = -(-p * (cfg.T + cfg.decode_steps + Tq) // qd)
+    g = torch.Generator(device="cuda").manual_seed(4321 + cfg.cid)
+    k = (torch.randn((B, H, rows, D), generator=g, device="cuda") * 1.5).to(dt)
+    v = torch.randn((B, H, rows, D), generator=g, device="cuda").to(dt)
+    k[:, :, 0] *= 8
+    k[:, :, L:] = float("nan")      # spare rows of the buffer are never read
+    v[:, :, L:] = float("nan")
+    q = torch.randn((B, H, Tq, D), generator=g, device="cuda").to(dt)
+    out = torch.empty((B, H, Tq, D), dtype=dt, device="cuda")
+    lse = torch.empty((B, H, Tq), dtype=torch.float32, device="cuda")
+    score = torch.empty((B, 1, L), dtype=torch.float32, device="cuda")
+    ws = ec.new_workspace(ec.EC_FN_PREFILL_SCORE, B, H, L, D, ec.EC_BF16)
+    ec.ec_chunk_score(q, k, v, P, out, lse, score, cfg.scale, ws)
+    torch.cuda.synchronize()
+    del ws
+    sc = _host(score)
+    np.testing.assert_allclose(sc.sum(-1), Tq, rtol=2e-5)
+    assert np.isfinite(sc).all() and (sc[..., -1] <= 1.0 + 1e-5).all()
+
+    weights = torch.randint(1, 30, (B, 1, L), generator=g, device="cuda", dtype=torch.int32)
+    weights[:, :, P:] = 1
+    for b in SAMPLES[name]:
+        qb, kb, vb = _host(q[b:b + 1]), _host(k[b:b + 1, :, :L]), _host(v[b:b + 1, :, :L])
+        ref = oracle.chunk_score(qb, kb, vb, P, cfg.scale, 1)
+        assert_close(to_host(out[b:b + 1]), ref["out"], cfg.dtype, f"out[{b}]")
+        assert_close(to_host(lse[b:b + 1]), ref["lse"], cfg.dtype, f"lse[{b}]")
+        assert_close(sc[b:b + 1], ref["score"], cfg.dtype, f"score[{b}]")
+        sc32 = ref["score"].astype(np.float32)
+        a_ref = oracle.select_anchors(sc32, n2, 1, 1)
+        a_gpu = torch.empty((1, 1, n2), dtype=torch.int32, device="cuda")
+        ec.ec_select_anchors(torch.from_numpy(sc32).cuda(), n2, 1, 1, a_gpu)
+        np.testing.assert_array_equal(a_gpu.cpu().numpy(), a_ref)
+        assign, _ = oracle.assign_nearest(a_ref, L)
+        wb = weights[b:b + 1].cpu().numpy()
+        ok, wsum = oracle.merge_weighted(kb, assign, wb, n2)
+        ov, _ = oracle.merge_weighted(vb, assign, wb, n2)
+        nk = torch.zeros((1, H, n2, D), dtype=dt, device="cuda")
+        nv = torch.zeros_like(nk)
+        d_counts = torch.empty((1, 1, n2), dtype=torch.int32, device="cuda")
+        ec.ec_remerge_compact(k[b:b + 1].contiguous(), v[b:b + 1].contiguous(), L, a_gpu, nk, nv,
+                              weights=weights[b:b + 1].contiguous(), counts=d_counts)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(d_counts.cpu().numpy(), wsum)
+        assert_close(to_host(nk), ok, cfg.dtype, "k_cache", stored=True)
+        assert_close(to_host(nv), ov, cfg.dtype, "v_cache", stored=True)
+
+    # whole batch on the GPU's own scores: structure at full size
+    anchors = torch.empty((B, 1, n2), dtype=torch.int32, device="cuda")
+    ec.ec_select_anchors(score, n2, 1, 1, anchors)
+    nk = torch.zeros((B, H, n2, D), dtype=dt, device="cuda")
+    nv = torch.zeros_like(nk)
+    counts = torch.empty((B, 1, n2), dtype=torch.int32, device="cuda")
+    ec.ec_remerge_compact(k, v, L, anchors, nk, nv, weights=weights, counts=counts)
+    torch.cuda.synchronize()
+    a = anchors.cpu().numpy()
+    assert (np.diff(a, axis=-1) > 0).all() and (a[..., 0] == 0).all() and (a[..., -1] == L - 1).all()
+    _assert_valid_selection(sc, a)
+    np.testing.assert_array_equal(counts.cpu().numpy().sum(-1), weights.cpu().numpy().sum(-1))
+    assert torch.isfinite(nk.float()).all() and torch.isfinite(nv.float()).all()
