@@ -202,3 +202,37 @@ def decode_step(q, k_new, v_new, k_cache, v_cache, pos, cache_len: int, evict_id
     if rc:
         raise ValueError(f"oracle_decode_step rc={rc}")
     return out, probs
+
+
+def decode_score_step(q, k_new, v_new, k_cache, v_cache, pos, freq, cache_len: int, new_pos: int, scale: float):
+    """Frequency policy: one generation step without removal that also adds its attention row to freq.
+
+    k_cache/v_cache fp64 [B,H,cap,D], pos int32 [B,G,cap] or None, freq fp64 [B,G,cap], all in place.
+    Returns (out [B,H,D], probs [B,H,cache_len+1]).
+    """
+    assert freq.dtype == np.float64 and freq.flags.c_contiguous
+    B, H, cap, D = k_cache.shape
+    G = freq.shape[1]
+    out, probs = decode_step(q, k_new, v_new, k_cache, v_cache, pos, cache_len, -1, new_pos, scale, want_probs=True)
+    rc = _load().oracle_freq_accumulate(_d(probs), B, H, G, cache_len + 1, cap, _d(freq))
+    if rc:
+        raise ValueError(f"oracle_freq_accumulate rc={rc}")
+    return out, probs
+
+
+def evict_min(freq_f32, k_cache, v_cache, pos, length: int, protect_first: int = 1, protect_recent: int = 1):
+    """Frequency policy: remove the row of least fp32 mass (lowest index among equals), in place.
+
+    freq_f32 float32 [B,G,cap]; k_cache/v_cache fp64 [B,H,cap,D]; pos int32 [B,G,cap] or None.  Returns victim [B,G].
+    """
+    assert freq_f32.dtype == np.float32 and freq_f32.flags.c_contiguous
+    for c in (k_cache, v_cache):
+        assert c.dtype == np.float64 and c.flags.c_contiguous
+    B, H, cap, D = k_cache.shape
+    G = freq_f32.shape[1]
+    victim = np.empty((B, G), np.int32)
+    rc = _load().oracle_evict_min(freq_f32.ctypes.data_as(_fp), _d(k_cache), _d(v_cache), _i(pos), B, H, G, D, cap,
+                                  length, protect_first, protect_recent, _i(victim))
+    if rc:
+        raise ValueError(f"oracle_evict_min rc={rc}")
+    return victim

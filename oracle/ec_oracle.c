@@ -36,6 +36,15 @@
  *    sequence.  A count-weighted mean (each row weighted by the number of
  *    original tokens it already stands for) is offered beside it as an extension.
  *  - decode order: append the new row, attend over all rows, then remove one row.
+ *  - "Frequency" discard policy during generation (the Frequency Cache of Sec. 4.1
+ *    Baselines, ablation row of Table 3a): every cached row carries the attention
+ *    mass it has received so far (layer-wise: the head mean, like the prompt
+ *    metric); each generated token adds its attention row to it; when a row must
+ *    go, the row with the least mass goes.  The paper leaves open: where a new
+ *    row's count starts (here: at the mass it receives from its own query), which
+ *    rows are exempt (here: the first protect_first and the newest protect_recent
+ *    rows, arguments), and ties (here: the lowest index).  The comparison is made
+ *    on fp32 values, the precision the counts are kept in.
  *  - retention test: evict iff the cache is longer than ceil(gamma*n) (Alg. 1's
  *    int(seq_len - n(1-r)) >= 1); truncation location = R rows before the newest
  *    row (R = 25 in Sec. 4.1), or an absolute location N_tl (Sec. 3.3 text).
@@ -500,5 +509,72 @@ int oracle_decode_step(const double *q, const double *k_new, const double *v_new
                         (size_t)(cache_len - evict_idx) * sizeof(int32_t));
         }
     }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Frequency policy, part 1 (Sec. 4.1 Baselines "Frequency Cache ... records   */
+/* how often each key-value pair is accessed ... continuously updates the      */
+/* frequency counts throughout the generation"): add one generation step's     */
+/* attention row to the per-row mass.                                         */
+/* probs [B,H,n] (this step's softmax rows), freq [B,G,cap] updated in place: */
+/* rows 0..n-2 += mass, row n-1 (the row just appended) = its mass.           */
+/* G == 1: mass = mean over heads; G == H: the head's own probability.        */
+/* ------------------------------------------------------------------------- */
+int oracle_freq_accumulate(const double *probs, int B, int H, int G, int n, int cap, double *freq)
+{
+    if (B < 1 || H < 1 || n < 1 || n > cap || (G != 1 && G != H)) return 1;
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < G; ++g)
+            for (int j = 0; j < n; ++j) {
+                double mass;
+                if (G == H) {
+                    mass = probs[((size_t)b * H + g) * n + j];
+                } else {
+                    mass = 0.0;
+                    for (int h = 0; h < H; ++h) mass += probs[((size_t)b * H + h) * n + j];
+                    mass /= (double)H;
+                }
+                double *f = freq + ((size_t)b * G + g) * cap + j;
+                *f = (j == n - 1) ? mass : *f + mass;
+            }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Frequency policy, part 2 ("selects the least frequently accessed key-value  */
+/* pairs for eviction"): per (b,g) the victim is the row of least mass among   */
+/* rows protect_first .. len-1-protect_recent, the lowest index among equals,  */
+/* compared as fp32 values.  The row is removed from k_cache, v_cache          */
+/* [B,H,cap,D], pos [B,G,cap] (may be NULL) and freq [B,G,cap] float; rows     */
+/* behind it move up by one.  victim [B,G] receives the index.                 */
+/* ------------------------------------------------------------------------- */
+int oracle_evict_min(float *freq, double *k_cache, double *v_cache, int32_t *pos, int B, int H,
+                     int G, int D, int cap, int len, int protect_first, int protect_recent,
+                     int32_t *victim)
+{
+    if (B < 1 || H < 1 || D < 1 || (G != 1 && G != H) || len < 1 || len > cap) return 1;
+    if (protect_first < 0 || protect_recent < 0 || protect_first + protect_recent >= len) return 1;
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < G; ++g) {
+            float *f = freq + ((size_t)b * G + g) * cap;
+            int best = protect_first;
+            for (int j = protect_first + 1; j <= len - 1 - protect_recent; ++j)
+                if (f[j] < f[best]) best = j;
+            victim[(size_t)b * G + g] = best;
+            for (int j = best; j + 1 < len; ++j) f[j] = f[j + 1];
+            if (pos) {
+                int32_t *p = pos + ((size_t)b * G + g) * cap;
+                for (int j = best; j + 1 < len; ++j) p[j] = p[j + 1];
+            }
+            for (int h = (G == H ? g : 0); h < (G == H ? g + 1 : H); ++h) {
+                double *kc = k_cache + ((size_t)b * H + h) * cap * D;
+                double *vc = v_cache + ((size_t)b * H + h) * cap * D;
+                memmove(kc + (size_t)best * D, kc + (size_t)(best + 1) * D,
+                        (size_t)(len - 1 - best) * D * sizeof(double));
+                memmove(vc + (size_t)best * D, vc + (size_t)(best + 1) * D,
+                        (size_t)(len - 1 - best) * D * sizeof(double));
+            }
+        }
     return 0;
 }

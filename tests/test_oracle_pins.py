@@ -415,3 +415,62 @@ def test_merge_weighted_two_levels_equal_one_level():
     assert np.abs(plain - direct).max() > 1e-3  # the unweighted mean of means differs
     # first moment conservation: sum_k wsum_k * row_k = sum_t x_t
     np.testing.assert_allclose((level2 * wsum[0, 0][None, None, :, None]).sum(2), x.sum(2), atol=1e-12)
+
+
+# ----------------------------------------------------------------- frequency discard policy (Table 3a "Frequency")
+def test_frequency_counts_are_the_column_sums_of_the_generated_rows():
+    # Starting from zero counts, Tq generation steps over P cached rows accumulate exactly the column
+    # sums of the Tq x (P+Tq) attention matrix, i.e. chunk_score's scores (itself pinned to library SDPA).
+    B, H, P, Tq, D, scale = 2, 3, 9, 7, 5, 0.6
+    q, k, v = _rand((B, H, Tq, D), 51), _rand((B, H, P + Tq, D), 52), _rand((B, H, P + Tq, D), 53)
+    for G in (1, H):
+        cap = P + Tq + 1
+        kc = np.zeros((B, H, cap, D)); vc = np.zeros_like(kc)
+        kc[:, :, :P] = k[:, :, :P]; vc[:, :, :P] = v[:, :, :P]
+        freq = np.zeros((B, G, cap))
+        outs = []
+        for t in range(Tq):
+            o, _ = oracle.decode_score_step(q[:, :, t], k[:, :, P + t], v[:, :, P + t], kc, vc, None, freq, P + t, 0, scale)
+            outs.append(o)
+        ref = oracle.chunk_score(q, k, v, P, scale, G)
+        np.testing.assert_allclose(freq[:, :, :P + Tq], ref["score"], atol=1e-13)
+        np.testing.assert_allclose(np.stack(outs, 2), ref["out"], atol=1e-13)
+        assert (freq[:, :, P + Tq:] == 0).all()
+
+
+def test_frequency_update_by_hand():
+    # two heads, three rows, hand-made probabilities: layer-wise mass is the head mean; the newest row is set
+    probs = np.array([[[0.5, 0.25, 0.25], [0.1, 0.3, 0.6]]])          # [B=1,H=2,n=3]
+    lib = oracle._load()
+    f1 = np.array([[[1.0, 2.0, 99.0, 7.0]]])                            # cap 4; row 2 is the new one, row 3 unused
+    assert lib.oracle_freq_accumulate(oracle._d(probs), 1, 2, 1, 3, 4, oracle._d(f1)) == 0
+    np.testing.assert_allclose(f1, [[[1.3, 2.275, 0.425, 7.0]]], atol=1e-15)
+    fh = np.array([[[1.0, 2.0, 99.0, 7.0], [0.0, 0.0, 99.0, 7.0]]])
+    assert lib.oracle_freq_accumulate(oracle._d(probs), 1, 2, 2, 3, 4, oracle._d(fh)) == 0
+    np.testing.assert_allclose(fh, [[[1.5, 2.25, 0.25, 7.0], [0.1, 0.3, 0.6, 7.0]]], atol=1e-15)
+
+
+@pytest.mark.parametrize("G", [1, 3])
+def test_evict_min_against_numpy(G):
+    B, H, D, cap, length, pf, pr = 2, 3, 4, 12, 10, 1, 2
+    rng = np.random.default_rng(60 + G)
+    kc, vc = rng.standard_normal((B, H, cap, D)), rng.standard_normal((B, H, cap, D))
+    pos = np.tile(np.arange(cap, dtype=np.int32) * 3, (B, G, 1))
+    freq = rng.random((B, G, cap)).astype(np.float32)
+    freq[0, 0, 0] = -1.0          # protected: never chosen although smallest
+    freq[0, 0, 9] = -1.0          # newest rows are protected too
+    freq[1, 0, 3] = freq[1, 0, 6] = 0.0   # tie: the lower index goes
+    k0, v0, p0, f0 = kc.copy(), vc.copy(), pos.copy(), freq.copy()
+    victim = oracle.evict_min(freq, kc, vc, pos, length, pf, pr)
+    for b in range(B):
+        for g in range(G):
+            want = pf + int(np.argmin(f0[b, g, pf:length - pr]))      # first occurrence of the minimum
+            assert victim[b, g] == want
+            np.testing.assert_array_equal(freq[b, g, :length - 1], np.delete(f0[b, g, :length], want))
+            np.testing.assert_array_equal(pos[b, g, :length - 1], np.delete(p0[b, g, :length], want))
+            for h in ([g] if G == H else range(H)):
+                np.testing.assert_array_equal(kc[b, h, :length - 1], np.delete(k0[b, h, :length], want, axis=0))
+                np.testing.assert_array_equal(vc[b, h, :length - 1], np.delete(v0[b, h, :length], want, axis=0))
+    assert victim[1, 0] == 3
+    with pytest.raises(ValueError):
+        oracle.evict_min(freq, kc, vc, pos, 3, 2, 1)   # nothing left to choose from
