@@ -49,7 +49,9 @@ typedef enum {
     EC_FN_PREFILL_SCORE = 0,
     EC_FN_SELECT_ANCHORS = 1,
     EC_FN_MERGE_COMPACT = 2,
-    EC_FN_DECODE_STEP = 3
+    EC_FN_DECODE_STEP = 3,
+    EC_FN_DECODE_SCORE_STEP = 4,
+    EC_FN_EVICT_MIN = 5
 } ec_fn;
 
 /* Budget rule of the retention test (Sec. 3.3 Output Generation; Alg. 1). */
@@ -75,7 +77,7 @@ const char* ec_status_string(int status);
 
 /*
  * Bytes of workspace the given entry point needs for these shapes.  Host, pure.
- * For EC_FN_DECODE_STEP pass T = cap.  Returns 0 for entry points that need none
+ * For EC_FN_DECODE_STEP and EC_FN_DECODE_SCORE_STEP pass T = cap.  Returns 0 for entry points that need none
  * and (size_t)-1 for unsupported shapes.
  */
 size_t ec_workspace_bytes(int fn, int B, int H, int T, int D, int dt);
@@ -232,6 +234,43 @@ int ec_decode_step(const void* q, const void* k_new, const void* v_new, void* k_
                    void* v_cache, int32_t* pos, int B, int H, int G, int D, int cap, int cache_len,
                    int evict_idx, int32_t new_pos, float scale, int dt, void* out, void* ws,
                    size_t ws_bytes, void* stream);
+
+/*
+ * The "Frequency" discard policy of the generation stage -- the Frequency Cache of Sec. 4.1 Baselines that
+ * the ablation of Table 3a ("Discard Position") compares the fixed-point elimination with: every cached
+ * row carries the attention mass it has received, every generated token adds its attention row to it,
+ * and when a row has to go the row of least mass goes.  Two calls per generated token:
+ *
+ * ec_decode_score_step = steps 1 and 2 of ec_decode_step (append, attend; no removal) plus
+ *     freq[b,g,j] += p_j for rows j < cache_len,   freq[b,g,cache_len] = p_{cache_len}
+ * where p is this step's softmax row of head g (G == H) or its mean over the heads, added in ascending head
+ * order (G == 1, the layer-wise metric of Sec. 3.3).  The new row's mass starts at what its own query
+ * gives it (the paper does not say where it starts).
+ *   freq   DEVICE [B,G,cap] float, updated in place (a compressed prompt's rows start at values of the
+ *          caller's choice, e.g. the importance scores of their anchors)
+ *   ws     DEVICE scratch, ec_workspace_bytes(EC_FN_DECODE_SCORE_STEP, B,H,cap,D,dt)
+ * All other arguments as in ec_decode_step.  The cache then holds cache_len + 1 rows.
+ */
+int ec_decode_score_step(const void* q, const void* k_new, const void* v_new, void* k_cache,
+                         void* v_cache, int32_t* pos, float* freq, int B, int H, int G, int D, int cap,
+                         int cache_len, int32_t new_pos, float scale, int dt, void* out, void* ws,
+                         size_t ws_bytes, void* stream);
+
+/*
+ * ec_evict_min removes, for every (b,g), the row of least mass among rows protect_first ..
+ * len-1-protect_recent (masses compared as fp32 values, -0 == +0, the lowest index among equals; NaN is
+ * outside the domain) from k_cache, v_cache, pos and freq; the rows behind it move up by one, so the cache
+ * then holds len - 1 rows.  Whether a row has to go is the caller's retention test (ec_evict_index >= 0).
+ *   k_cache,v_cache  DEVICE [B,H,cap,D] dt, updated in place
+ *   pos              DEVICE [B,G,cap] int32, updated; may be NULL
+ *   freq             DEVICE [B,G,cap] float, updated
+ *   victim           DEVICE [B,G] int32, written: the index removed
+ * Requires 1 <= len <= cap and protect_first + protect_recent < len.  The victim differs between batch
+ * elements (and heads when G == H), but every (b,h) loses exactly one row, so len stays common.
+ */
+int ec_evict_min(void* k_cache, void* v_cache, int32_t* pos, float* freq, int B, int H, int G, int D,
+                 int cap, int len, int protect_first, int protect_recent, int dt, int32_t* victim,
+                 void* stream);
 
 #ifdef __cplusplus
 }

@@ -16,13 +16,15 @@ LIB_PATH = os.environ.get("EC_LIB_PATH", os.path.join(_HERE, "libelastic_cache.s
 
 EC_OK, EC_EINVAL, EC_EUNSUPPORTED, EC_EWORKSPACE, EC_EDEVICE = range(5)
 EC_F32, EC_BF16 = 0, 1
-EC_FN_PREFILL_SCORE, EC_FN_SELECT_ANCHORS, EC_FN_MERGE_COMPACT, EC_FN_DECODE_STEP = range(4)
+(EC_FN_PREFILL_SCORE, EC_FN_SELECT_ANCHORS, EC_FN_MERGE_COMPACT, EC_FN_DECODE_STEP, EC_FN_DECODE_SCORE_STEP,
+ EC_FN_EVICT_MIN) = range(6)
 EC_BUDGET_RATIO, EC_BUDGET_FIXED = 0, 1
 EC_TRUNC_RECENT, EC_TRUNC_ABS = 0, 1
 EC_MERGE_MEAN, EC_MERGE_EVICT = 0, 1
 
 SYMBOLS = ("ec_status_string", "ec_workspace_bytes", "ec_prefill_score", "ec_chunk_score", "ec_select_anchors",
-           "ec_merge_compact", "ec_remerge_compact", "ec_evict_index", "ec_decode_step")
+           "ec_merge_compact", "ec_remerge_compact", "ec_evict_index", "ec_decode_step", "ec_decode_score_step",
+           "ec_evict_min")
 
 _lib = None
 
@@ -62,6 +64,10 @@ def load():
     lib.ec_evict_index.restype = c_int
     lib.ec_decode_step.argtypes = ([c_vp] * 6 + [c_int] * 7 + [ctypes.c_int32, c_f, c_int, c_vp, c_vp, c_sz, c_vp])
     lib.ec_decode_step.restype = c_int
+    lib.ec_decode_score_step.argtypes = ([c_vp] * 7 + [c_int] * 6 + [ctypes.c_int32, c_f, c_int, c_vp, c_vp, c_sz, c_vp])
+    lib.ec_decode_score_step.restype = c_int
+    lib.ec_evict_min.argtypes = [c_vp] * 4 + [c_int] * 9 + [c_vp, c_vp]
+    lib.ec_evict_min.restype = c_int
     _lib = lib
     return lib
 
@@ -196,4 +202,31 @@ def ec_decode_step(q, k_new, v_new, k_cache, v_cache, pos, cache_len: int, evict
                                0 if ws is None else ws.numel() * ws.element_size(), _stream())
     if check and rc != EC_OK:
         raise EcError("ec_decode_step", rc)
+    return rc
+
+
+def ec_decode_score_step(q, k_new, v_new, k_cache, v_cache, pos, freq, cache_len: int, new_pos: int, scale: float,
+                         out, ws, check=True) -> int:
+    """Frequency policy: append + attend + add the attention row to freq [B,G,cap] f32 (no removal)."""
+    B, H, cap, D = k_cache.shape
+    G = freq.shape[1]
+    rc = load().ec_decode_score_step(_ptr(q, "q"), _ptr(k_new, "k_new"), _ptr(v_new, "v_new"), _ptr(k_cache, "k_cache"),
+                                     _ptr(v_cache, "v_cache"), _ptr(pos, "pos"), _ptr(freq, "freq"), B, H, G, D, cap,
+                                     cache_len, new_pos, scale, dtype_code(k_cache), _ptr(out, "out"), _ptr(ws, "ws"),
+                                     0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    if check and rc != EC_OK:
+        raise EcError("ec_decode_score_step", rc)
+    return rc
+
+
+def ec_evict_min(k_cache, v_cache, pos, freq, length: int, protect_first: int, protect_recent: int, victim,
+                 check=True) -> int:
+    """Frequency policy: remove the least-mass row of every (b,g); victim [B,G] int32 receives the index."""
+    B, H, cap, D = k_cache.shape
+    G = freq.shape[1]
+    rc = load().ec_evict_min(_ptr(k_cache, "k_cache"), _ptr(v_cache, "v_cache"), _ptr(pos, "pos"), _ptr(freq, "freq"),
+                             B, H, G, D, cap, length, protect_first, protect_recent, dtype_code(k_cache),
+                             _ptr(victim, "victim"), _stream())
+    if check and rc != EC_OK:
+        raise EcError("ec_evict_min", rc)
     return rc

@@ -28,11 +28,15 @@ template <int DT, int D, int WAVES, int UNROLL> struct DecodeShape {
     static constexpr int kTile = WAVES * UNROLL * kRPW;       // rows per workgroup iteration
 };
 
-template <int DT, int D, int WAVES, int UNROLL>
+// EMIT (frequency discard policy): the kernel also stores every row's scaled score (base-2 units) into
+// raw [B,H,cap] and the head's softmax maximum and denominator into stats [B,H,2], from which
+// freq_accumulate_kernel forms this step's probabilities.
+template <int DT, int D, int WAVES, int UNROLL, bool EMIT>
 __global__ __launch_bounds__(WAVES * kWave) void decode_step_kernel(
     const uint4* __restrict__ q, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
     uint4* k_cache, uint4* v_cache, int32_t* pos, uint4* __restrict__ out, int H, int G, int cap,
-    int cache_len, int evict_idx, int32_t new_pos, float scale_log2e)
+    int cache_len, int evict_idx, int32_t new_pos, float scale_log2e, float* __restrict__ raw,
+    float* __restrict__ stats)
 {
     using S = DecodeShape<DT, D, WAVES, UNROLL>;
     constexpr int kDecodeUnroll = UNROLL;
@@ -108,6 +112,7 @@ __global__ __launch_bounds__(WAVES * kWave) void decode_step_kernel(
             for (int e = 0; e < EPL; ++e) d = fmaf(qf[e], kx[e], d);
             d = group_sum<LPR>(d);
             s[u] = (r >= 0) ? d : -INFINITY;
+            if (EMIT && r >= 0 && sub == 0) raw[(size_t)bh * cap + r] = d;
             m_tile = fmaxf(m_tile, s[u]);
         }
         const float m_new = fmaxf(m_run, m_tile);
@@ -175,6 +180,10 @@ __global__ __launch_bounds__(WAVES * kWave) void decode_step_kernel(
             const float wt = (sh_m[w] > -INFINITY) ? exp2f(sh_m[w] - M) : 0.f;
             L = fmaf(sh_l[w], wt, L);
             o_d = fmaf(sh_acc[w][tid], wt, o_d);
+        }
+        if (EMIT && tid == 0) {
+            stats[(size_t)bh * 2] = M;
+            stats[(size_t)bh * 2 + 1] = L;
         }
         const float r = o_d / L;
         typename Elem<DT>::type* o = reinterpret_cast<typename Elem<DT>::type*>(out) + (size_t)bh * D;
@@ -246,10 +255,10 @@ static int launch_decode_w(const void* q, const void* k_new, const void* v_new, 
                            int evict_idx, int32_t new_pos, float scale, void* out, hipStream_t stream)
 {
     using S = DecodeShape<DT, D, WAVES, UNROLL>;
-    hipLaunchKernelGGL((decode_step_kernel<DT, D, WAVES, UNROLL>), dim3(B * H), dim3(S::kThreads), 0, stream,
+    hipLaunchKernelGGL((decode_step_kernel<DT, D, WAVES, UNROLL, false>), dim3(B * H), dim3(S::kThreads), 0, stream,
                        (const uint4*)q, (const uint4*)k_new, (const uint4*)v_new, (uint4*)k_cache,
                        (uint4*)v_cache, pos, (uint4*)out, H, G, cap, cache_len, evict_idx, new_pos,
-                       scale * kLog2e);
+                       scale * kLog2e, (float*)nullptr, (float*)nullptr);
     return status_from_hip(hipGetLastError());
 }
 
@@ -295,6 +304,196 @@ int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k
     EC_DECODE_CASE(EC_F32, 64)
 #undef EC_DECODE_CASE
     return EC_EUNSUPPORTED;
+}
+
+// ------------------------------------------------------------------ frequency discard policy
+// freq[b,g,j] += this step's attention mass of row j (head mean when G == 1, heads added in ascending
+// order); the row just appended (j = n - 1) starts at its own mass.
+__global__ __launch_bounds__(256) void freq_accumulate_kernel(const float* __restrict__ raw,
+                                                              const float* __restrict__ stats,
+                                                              float* __restrict__ freq, int H, int G, int n, int cap)
+{
+    const int bg = blockIdx.y;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n) return;
+    const int b = bg / G, g = bg % G;
+    float mass;
+    if (G == H) {
+        const size_t bh = (size_t)b * H + g;
+        mass = exp2f(raw[bh * cap + j] - stats[bh * 2]) / stats[bh * 2 + 1];
+    } else {
+        float acc = 0.f;
+        for (int h = 0; h < H; ++h) {
+            const size_t bh = (size_t)b * H + h;
+            acc += exp2f(raw[bh * cap + j] - stats[bh * 2]) / stats[bh * 2 + 1];
+        }
+        mass = acc / (float)H;
+    }
+    float* f = freq + (size_t)bg * cap + j;
+    *f = (j == n - 1) ? mass : *f + mass;
+}
+
+template <int DT, int D, int WAVES>
+static int launch_decode_score(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                               int32_t* pos, float* freq, int B, int H, int G, int cap, int cache_len,
+                               int32_t new_pos, float scale, void* out, float* raw, float* stats,
+                               hipStream_t stream)
+{
+    using S = DecodeShape<DT, D, WAVES, 4>;
+    hipLaunchKernelGGL((decode_step_kernel<DT, D, WAVES, 4, true>), dim3(B * H), dim3(S::kThreads), 0, stream,
+                       (const uint4*)q, (const uint4*)k_new, (const uint4*)v_new, (uint4*)k_cache,
+                       (uint4*)v_cache, pos, (uint4*)out, H, G, cap, cache_len, -1, new_pos, scale * kLog2e, raw,
+                       stats);
+    int rc = status_from_hip(hipGetLastError());
+    if (rc != EC_OK) return rc;
+    const int n = cache_len + 1;
+    hipLaunchKernelGGL(freq_accumulate_kernel, dim3((n + 255) / 256, B * G), dim3(256), 0, stream, raw, stats, freq,
+                       H, G, n, cap);
+    return status_from_hip(hipGetLastError());
+}
+
+int decode_score_dispatch(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                          int32_t* pos, float* freq, int B, int H, int G, int D, int cap, int cache_len,
+                          int32_t new_pos, float scale, int dt, void* out, float* raw, float* stats,
+                          hipStream_t stream)
+{
+    const bool wide = cache_len + 1 >= 96;
+#define EC_DSCORE_CASE(DT_, D_)                                                                                \
+    if (dt == DT_ && D == D_)                                                                                  \
+        return wide ? launch_decode_score<DT_, D_, 8>(q, k_new, v_new, k_cache, v_cache, pos, freq, B, H, G, cap,  \
+                                                      cache_len, new_pos, scale, out, raw, stats, stream)     \
+                    : launch_decode_score<DT_, D_, 4>(q, k_new, v_new, k_cache, v_cache, pos, freq, B, H, G, cap,  \
+                                                      cache_len, new_pos, scale, out, raw, stats, stream);
+    EC_DSCORE_CASE(EC_BF16, 128)
+    EC_DSCORE_CASE(EC_BF16, 64)
+    EC_DSCORE_CASE(EC_F32, 128)
+    EC_DSCORE_CASE(EC_F32, 64)
+#undef EC_DSCORE_CASE
+    return EC_EUNSUPPORTED;
+}
+
+// Least-mass row of one score group: lowest index among equal fp32 values, rows [lo, hi] only.
+__device__ __forceinline__ int argmin_row(const float* __restrict__ f, int lo, int hi, int tid, int threads,
+                                          float* sh_v, int* sh_i)
+{
+    float bv = INFINITY;
+    int bi = 0x7fffffff;
+    for (int j = lo + tid; j <= hi; j += threads) {  // ascending per thread: strict < keeps the first
+        const float v = f[j];
+        if (v < bv || bi == 0x7fffffff) {
+            bv = v;
+            bi = j;
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const float ov = __shfl_xor(bv, off, kWave);
+        const int oi = __shfl_xor(bi, off, kWave);
+        if (oi != 0x7fffffff && (bi == 0x7fffffff || ov < bv || (ov == bv && oi < bi))) {
+            bv = ov;
+            bi = oi;
+        }
+    }
+    const int wave = tid / kWave, lane = tid % kWave;
+    if (lane == 0) {
+        sh_v[wave] = bv;
+        sh_i[wave] = bi;
+    }
+    __syncthreads();
+    bv = sh_v[0];
+    bi = sh_i[0];
+    for (int w = 1; w < threads / kWave; ++w) {
+        const float ov = sh_v[w];
+        const int oi = sh_i[w];
+        if (oi != 0x7fffffff && (bi == 0x7fffffff || ov < bv || (ov == bv && oi < bi))) {
+            bv = ov;
+            bi = oi;
+        }
+    }
+    return bi;
+}
+
+constexpr int kEvictThreads = 256;
+constexpr int kEvictUnroll = 4;
+
+// Every (b,h) workgroup finds its group's victim itself (freq is only read here) and moves its own K and V
+// rows up by one; the group's first head also publishes the index.
+__global__ __launch_bounds__(kEvictThreads) void evict_min_rows_kernel(uint4* k_cache, uint4* v_cache,
+                                                                       const float* __restrict__ freq,
+                                                                       int32_t* __restrict__ victim, int H, int G,
+                                                                       int cap, int len, int lo, int hi, int lpr)
+{
+    __shared__ float sh_v[kEvictThreads / kWave];
+    __shared__ int sh_i[kEvictThreads / kWave];
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    const int b = bh / H, h = bh % H;
+    const size_t bg = (size_t)b * G + (G == 1 ? 0 : h);
+    const int vic = argmin_row(freq + bg * cap, lo, hi, tid, kEvictThreads, sh_v, sh_i);
+    if (tid == 0 && (G == H || h == 0)) victim[bg] = vic;
+
+    uint4* kc = k_cache + (size_t)bh * cap * lpr;
+    uint4* vc = v_cache + (size_t)bh * cap * lpr;
+    const int total = (len - 1 - vic) * lpr;  // 16-byte chunks that move, in ascending address order
+    for (int c0 = 0; c0 < total; c0 += kEvictThreads * kEvictUnroll) {
+        uint4 kk[kEvictUnroll], vv[kEvictUnroll];
+#pragma unroll
+        for (int u = 0; u < kEvictUnroll; ++u) {
+            const int c = c0 + u * kEvictThreads + tid;
+            if (c < total) {
+                kk[u] = kc[(size_t)(vic + 1) * lpr + c];
+                vv[u] = vc[(size_t)(vic + 1) * lpr + c];
+            }
+        }
+        __syncthreads();  // the slab is read completely before any of it is overwritten
+#pragma unroll
+        for (int u = 0; u < kEvictUnroll; ++u) {
+            const int c = c0 + u * kEvictThreads + tid;
+            if (c < total) {
+                kc[(size_t)vic * lpr + c] = kk[u];
+                vc[(size_t)vic * lpr + c] = vv[u];
+            }
+        }
+        __syncthreads();  // and written before the next slab, which overlaps it by one row, is read
+    }
+}
+
+// The group's positions and masses follow their rows.
+__global__ __launch_bounds__(kEvictThreads) void evict_min_meta_kernel(float* freq, int32_t* pos,
+                                                                       const int32_t* __restrict__ victim, int cap,
+                                                                       int len)
+{
+    const int bg = blockIdx.x, tid = threadIdx.x;
+    const int vic = victim[bg];
+    float* f = freq + (size_t)bg * cap;
+    int32_t* p = pos ? pos + (size_t)bg * cap : nullptr;
+    const int total = len - 1 - vic;
+    for (int c0 = 0; c0 < total; c0 += kEvictThreads) {
+        const int c = c0 + tid;
+        float fv = 0.f;
+        int32_t pv = 0;
+        if (c < total) {
+            fv = f[vic + 1 + c];
+            if (p) pv = p[vic + 1 + c];
+        }
+        __syncthreads();
+        if (c < total) {
+            f[vic + c] = fv;
+            if (p) p[vic + c] = pv;
+        }
+        __syncthreads();
+    }
+}
+
+int evict_min_dispatch(void* k_cache, void* v_cache, int32_t* pos, float* freq, int B, int H, int G, int D, int cap,
+                       int len, int protect_first, int protect_recent, int dt, int32_t* victim, hipStream_t stream)
+{
+    const int lpr = D * (dt == EC_F32 ? 4 : 2) / 16;
+    hipLaunchKernelGGL(evict_min_rows_kernel, dim3(B * H), dim3(kEvictThreads), 0, stream, (uint4*)k_cache,
+                       (uint4*)v_cache, freq, victim, H, G, cap, len, protect_first, len - 1 - protect_recent, lpr);
+    int rc = status_from_hip(hipGetLastError());
+    if (rc != EC_OK) return rc;
+    hipLaunchKernelGGL(evict_min_meta_kernel, dim3(B * G), dim3(kEvictThreads), 0, stream, freq, pos, victim, cap, len);
+    return status_from_hip(hipGetLastError());
 }
 
 }  // namespace ec

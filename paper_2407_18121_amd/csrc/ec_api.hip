@@ -9,6 +9,12 @@ int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k
                     int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
                     int32_t new_pos, float scale, int dt, void* out, int forced_waves, int forced_unroll,
                     hipStream_t stream);
+int decode_score_dispatch(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                          int32_t* pos, float* freq, int B, int H, int G, int D, int cap, int cache_len,
+                          int32_t new_pos, float scale, int dt, void* out, float* raw, float* stats,
+                          hipStream_t stream);
+int evict_min_dispatch(void* k_cache, void* v_cache, int32_t* pos, float* freq, int B, int H, int G, int D, int cap,
+                       int len, int protect_first, int protect_recent, int dt, int32_t* victim, hipStream_t stream);
 int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, const int32_t* weights,
                    const int32_t* src_pos, int B, int H, int G, int T, int src_rows, int D, int n_anchor, int dt,
                    int evict_only, void* k_cache, void* v_cache, int cap, int32_t* counts, int32_t* assign,
@@ -103,6 +109,11 @@ size_t ec_workspace_bytes(int fn, int B, int H, int T, int D, int dt)
         case EC_FN_DECODE_STEP:
             if (!shape_supported(D, dt)) return (size_t)-1;
             return 0;  // one workgroup owns a whole (batch, head): nothing is staged in memory
+        case EC_FN_DECODE_SCORE_STEP:
+            if (!shape_supported(D, dt)) return (size_t)-1;
+            // every row's scaled score [B,H,T] + softmax maximum and denominator [B,H,2], fp32
+            return align256((size_t)B * H * T * sizeof(float)) + align256((size_t)B * H * 2 * sizeof(float));
+        case EC_FN_EVICT_MIN: return 0;
         default: return (size_t)-1;
     }
 }
@@ -211,6 +222,39 @@ int ec_decode_step(const void* q, const void* k_new, const void* v_new, void* k_
     return ec::decode_dispatch(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, D, cap, cache_len, evict_idx,
                                new_pos, scale, dt, out, env_int("EC_DECODE_WAVES", 0), env_int("EC_DECODE_UNROLL", 0),
                                reinterpret_cast<hipStream_t>(stream));
+}
+
+int ec_decode_score_step(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                         int32_t* pos, float* freq, int B, int H, int G, int D, int cap, int cache_len,
+                         int32_t new_pos, float scale, int dt, void* out, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!q || !k_new || !v_new || !k_cache || !v_cache || !freq || !out) return EC_EINVAL;
+    if (B < 1 || H < 1 || D < 1 || cap < 1) return EC_EINVAL;
+    if (G != 1 && G != H) return EC_EINVAL;
+    if (cache_len < 0 || cache_len >= cap) return EC_EINVAL;
+    if (!(scale == scale)) return EC_EINVAL;
+    if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
+    if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
+    const size_t need = ec_workspace_bytes(EC_FN_DECODE_SCORE_STEP, B, H, cap, D, dt);
+    if (!ws || ws_bytes < need) return EC_EWORKSPACE;
+    float* raw = reinterpret_cast<float*>(ws);
+    float* stats = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align256((size_t)B * H * cap * sizeof(float)));
+    return ec::decode_score_dispatch(q, k_new, v_new, k_cache, v_cache, pos, freq, B, H, G, D, cap, cache_len, new_pos,
+                                     scale, dt, out, raw, stats, reinterpret_cast<hipStream_t>(stream));
+}
+
+int ec_evict_min(void* k_cache, void* v_cache, int32_t* pos, float* freq, int B, int H, int G, int D, int cap,
+                 int len, int protect_first, int protect_recent, int dt, int32_t* victim, void* stream)
+{
+    if (!k_cache || !v_cache || !freq || !victim) return EC_EINVAL;
+    if (B < 1 || H < 1 || D < 1 || cap < 1) return EC_EINVAL;
+    if (G != 1 && G != H) return EC_EINVAL;
+    if (len < 1 || len > cap) return EC_EINVAL;
+    if (protect_first < 0 || protect_recent < 0 || (long long)protect_first + protect_recent >= len) return EC_EINVAL;
+    if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
+    if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
+    return ec::evict_min_dispatch(k_cache, v_cache, pos, freq, B, H, G, D, cap, len, protect_first, protect_recent, dt,
+                                  victim, reinterpret_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"
