@@ -9,7 +9,8 @@ resident in HBM before the timed region.  Prints ONE JSON line.
 
 After the timed region it also times, outside `value`, a second turn (`detail.turn2`): a new chunk of
 `--turn2` tokens (default: half the prompt) is encoded over the cache the generation left behind with
-ec_chunk_score -> ec_select_anchors -> ec_remerge_compact.
+ec_chunk_score -> ec_select_anchors -> ec_remerge_compact; and `--freq-steps` generated tokens under the
+"Frequency" discard policy (`detail.frequency_policy`: ec_decode_score_step + ec_evict_min per layer-step).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--score-mode layer|head]
                     [--no-graph] [--no-cpu-baseline] [--turn2 N]
@@ -48,6 +49,8 @@ def parse():
                     help="also launch one plain device copy of this many MiB (reference dispatch for HBM counters)")
     ap.add_argument("--turn2", type=int, default=-1,
                     help="tokens of the second-turn chunk timed after the main step (-1 = half the prompt, 0 = skip)")
+    ap.add_argument("--freq-steps", type=int, default=32,
+                    help="generated tokens timed under the frequency discard policy after the main step (0 = skip)")
     ap.add_argument("--distinct-layers", type=int, default=0,
                     help="distinct prompt tensors to generate (0 = one per layer; fewer are cycled)")
     return ap.parse_args()
@@ -221,6 +224,40 @@ class Turn2:
     def run_all(self, s):
         for a, b, c in zip(self.score_calls, self.select_calls, self.merge_calls):
             rc = self.lib.ec_chunk_score(*a, s) | self.lib.ec_select_anchors(*b, s) | self.lib.ec_remerge_compact(*c, s)
+            assert rc == 0, rc
+
+
+class FrequencyDecode:
+    """Generation under the "Frequency" discard policy (Table 3a) at a constant cache length: every layer-step is
+    ec_decode_score_step followed by ec_evict_min, on the caches the main step left."""
+
+    def __init__(self, wl, steps):
+        import torch
+        cfg, ec = wl.cfg, wl.ec
+        self.wl, self.lib = wl, wl.lib
+        B, H, D, L, G, cap = cfg.B, cfg.H, cfg.D, cfg.layers, wl.G, cfg.cap
+        N = min(wl.final_len, cap - 1)
+        self.N, self.steps = N, min(steps, cfg.decode_steps)
+        g = torch.Generator(device="cuda").manual_seed(7)
+        self.freq = [torch.rand((B, G, cap), generator=g, device="cuda") * 0.05 for _ in range(L)]
+        self.victim = torch.empty((B, G), dtype=torch.int32, device="cuda")
+        self.ws = ec.new_workspace(ec.EC_FN_DECODE_SCORE_STEP, B, H, cap, D, wl.dt_code)
+        ws, wsb = self.ws.data_ptr(), self.ws.numel()
+        self.calls = []
+        for step in range(self.steps):
+            for l in range(L):
+                dq, dk, dv = wl.dec[l]
+                self.calls.append(((dq[step].data_ptr(), dk[step].data_ptr(), dv[step].data_ptr(), wl.k_cache[l].data_ptr(),
+                                    wl.v_cache[l].data_ptr(), wl.pos[l].data_ptr(), self.freq[l].data_ptr(), B, H, G, D, cap,
+                                    N, cfg.T + step, cfg.scale, wl.dt_code, wl.dec_out.data_ptr(), ws, wsb),
+                                   (wl.k_cache[l].data_ptr(), wl.v_cache[l].data_ptr(), wl.pos[l].data_ptr(),
+                                    self.freq[l].data_ptr(), B, H, G, D, cap, N + 1, 1, 1, wl.dt_code, self.victim.data_ptr())))
+        self.bytes_per_layer_step = 2.0 * B * H * (N + 1) * D * cfg.esize
+
+    def run(self, s):
+        f, e = self.lib.ec_decode_score_step, self.lib.ec_evict_min
+        for a, b in self.calls:
+            rc = f(*a, s) | e(*b, s)
             assert rc == 0, rc
 
 
@@ -404,6 +441,24 @@ def main():
         do_prefill()
         torch.cuda.synchronize()
 
+    freq_detail = None
+    if args.freq_steps > 0:
+        print("[bench] frequency discard policy at constant cache length", file=sys.stderr, flush=True)
+        do_decode()
+        torch.cuda.synchronize()
+        fd = FrequencyDecode(wl, args.freq_steps)
+        fd.run(wl._stream())
+        torch.cuda.synchronize()
+        fn = (capture(torch, fd.run) if use_graph else None) or (lambda: fd.run(wl._stream()))
+        fn()
+        f_ms = timed(torch, fn, 3) / (fd.steps * L)
+        freq_detail = {"cache_rows": fd.N, "steps": fd.steps, "us_per_layer_step": f_ms * 1e3,
+                       "attn_GBps": fd.bytes_per_layer_step / (f_ms * 1e-3) / 1e9,
+                       "launches_per_layer_step": 4}
+        del fd
+        do_prefill()
+        torch.cuda.synchronize()
+
     n_dec = len(wl.decode_calls)
     dec_launch_us = decode_ms * 1e3 / n_dec
     dec_gbps = wl.decode_bytes / (decode_ms * 1e-3) / 1e9
@@ -446,6 +501,8 @@ def main():
     }
     if turn2 is not None:
         res["detail"]["turn2"] = turn2
+    if freq_detail is not None:
+        res["detail"]["frequency_policy"] = freq_detail
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         res["cpu_baseline"] = cpu_baseline(cfg, wl, wl.G)
