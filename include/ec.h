@@ -236,6 +236,39 @@ int ec_decode_step(const void* q, const void* k_new, const void* v_new, void* k_
                    size_t ws_bytes, void* stream);
 
 /*
+ * Ragged batches: the same four steps for a batch whose sequences differ in length (what a serving
+ * loop hands over; the paper's Alg. 1 treats one sequence, so each batch element simply follows it with
+ * its own numbers).  All tensors keep the padded shapes of the dense calls -- prompt tensors
+ * [B,H,T_max,D], scores [B,G,T_max], anchors and counts [B,G,n_max], caches [B,H,cap,D] -- and the
+ * per-sequence numbers are DEVICE int32 arrays of B entries, so a generation loop never has to
+ * synchronise with the host:
+ *   seq_len[b]      positions of batch element b (clamped into 0..T_max; 0 = nothing is done for b)
+ *   n_anchor_b[b]   anchors of b (clamped into 0..min(seq_len[b], n_max))
+ *   cache_len_b[b]  rows its cache holds before the step (clamped into 0..cap-1)
+ *   evict_idx_b[b]  row to remove after the step or -1 (clamped into -1..cache_len_b[b]); NULL = none
+ *   new_pos_b[b]    original position of the appended row (required when pos is given)
+ * For batch element b every result equals the dense call on that element alone with T = seq_len[b]
+ * (resp. n_anchor = n_anchor_b[b], cache_len = cache_len_b[b], ...).  Entries of the padded outputs beyond a
+ * sequence's own length (out, lse and score rows >= seq_len[b], anchors >= n_anchor_b[b], ...) are
+ * unspecified; padding rows of the inputs are never read.  protect_first / protect_last are common to the
+ * batch and are cut to n_anchor_b[b] where a sequence has fewer anchors.
+ */
+int ec_prefill_score_varlen(const void* q, const void* k, const void* v, void* out, float* lse,
+                            float* score, const int32_t* seq_len, int B, int H, int G, int T_max, int D,
+                            int dt, float scale, void* ws, size_t ws_bytes, void* stream);
+int ec_select_anchors_varlen(const float* score, const int32_t* seq_len, const int32_t* n_anchor_b, int B,
+                             int G, int T_max, int n_max, int protect_first, int protect_last,
+                             int32_t* anchor_idx, void* ws, size_t ws_bytes, void* stream);
+int ec_merge_compact_varlen(const void* k, const void* v, const int32_t* anchor_idx, const int32_t* seq_len,
+                            const int32_t* n_anchor_b, int B, int H, int G, int T_max, int D, int n_max,
+                            int dt, int merge_mode, void* k_cache, void* v_cache, int cap, int32_t* counts,
+                            int32_t* assign, int32_t* pos, void* stream);
+int ec_decode_step_varlen(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                          int32_t* pos, const int32_t* cache_len_b, const int32_t* evict_idx_b,
+                          const int32_t* new_pos_b, int B, int H, int G, int D, int cap, float scale, int dt,
+                          void* out, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * The "Frequency" discard policy of the generation stage -- the Frequency Cache of Sec. 4.1 Baselines that
  * the ablation of Table 3a ("Discard Position") compares the fixed-point elimination with: every cached
  * row carries the attention mass it has received, every generated token adds its attention row to it,

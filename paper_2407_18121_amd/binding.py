@@ -24,7 +24,8 @@ EC_MERGE_MEAN, EC_MERGE_EVICT = 0, 1
 
 SYMBOLS = ("ec_status_string", "ec_workspace_bytes", "ec_prefill_score", "ec_chunk_score", "ec_select_anchors",
            "ec_merge_compact", "ec_remerge_compact", "ec_evict_index", "ec_decode_step", "ec_decode_score_step",
-           "ec_evict_min")
+           "ec_evict_min", "ec_prefill_score_varlen", "ec_select_anchors_varlen", "ec_merge_compact_varlen",
+           "ec_decode_step_varlen")
 
 _lib = None
 
@@ -68,6 +69,14 @@ def load():
     lib.ec_decode_score_step.restype = c_int
     lib.ec_evict_min.argtypes = [c_vp] * 4 + [c_int] * 9 + [c_vp, c_vp]
     lib.ec_evict_min.restype = c_int
+    lib.ec_prefill_score_varlen.argtypes = [c_vp] * 7 + [c_int] * 6 + [c_f, c_vp, c_sz, c_vp]
+    lib.ec_prefill_score_varlen.restype = c_int
+    lib.ec_select_anchors_varlen.argtypes = [c_vp] * 3 + [c_int] * 6 + [c_vp, c_vp, c_sz, c_vp]
+    lib.ec_select_anchors_varlen.restype = c_int
+    lib.ec_merge_compact_varlen.argtypes = [c_vp] * 5 + [c_int] * 8 + [c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_vp]
+    lib.ec_merge_compact_varlen.restype = c_int
+    lib.ec_decode_step_varlen.argtypes = [c_vp] * 9 + [c_int] * 5 + [c_f, c_int, c_vp, c_vp, c_sz, c_vp]
+    lib.ec_decode_step_varlen.restype = c_int
     _lib = lib
     return lib
 
@@ -229,4 +238,67 @@ def ec_evict_min(k_cache, v_cache, pos, freq, length: int, protect_first: int, p
                              _ptr(victim, "victim"), _stream())
     if check and rc != EC_OK:
         raise EcError("ec_evict_min", rc)
+    return rc
+
+
+def _i32(t, name, n):
+    if t is None:
+        return None
+    if t.dtype != torch.int32 or t.numel() != n:
+        raise ValueError(f"{name} must be an int32 tensor of {n} entries")
+    return _ptr(t, name)
+
+
+def ec_prefill_score_varlen(q, k, v, out, lse, score, seq_len, scale: float, ws, check=True) -> int:
+    """Ragged batch: q,k,v [B,H,T_max,D], seq_len int32 [B] on the device."""
+    B, H, T, D = q.shape
+    G = score.shape[1]
+    rc = load().ec_prefill_score_varlen(_ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(out, "out"), _ptr(lse, "lse"),
+                                        _ptr(score, "score"), _i32(seq_len, "seq_len", B), B, H, G, T, D, dtype_code(q),
+                                        scale, _ptr(ws, "ws"), 0 if ws is None else ws.numel() * ws.element_size(),
+                                        _stream())
+    if check and rc != EC_OK:
+        raise EcError("ec_prefill_score_varlen", rc)
+    return rc
+
+
+def ec_select_anchors_varlen(score, seq_len, n_anchor_b, protect_first: int, protect_last: int, anchor_idx,
+                             check=True) -> int:
+    """Ragged batch: score [B,G,T_max], anchor_idx [B,G,n_max]; seq_len, n_anchor_b int32 [B] on the device."""
+    B, G, T = score.shape
+    rc = load().ec_select_anchors_varlen(_ptr(score, "score"), _i32(seq_len, "seq_len", B),
+                                         _i32(n_anchor_b, "n_anchor_b", B), B, G, T, anchor_idx.shape[2], protect_first,
+                                         protect_last, _ptr(anchor_idx, "anchor_idx"), None, 0, _stream())
+    if check and rc != EC_OK:
+        raise EcError("ec_select_anchors_varlen", rc)
+    return rc
+
+
+def ec_merge_compact_varlen(k, v, anchor_idx, seq_len, n_anchor_b, k_cache, v_cache, counts=None, assign=None, pos=None,
+                            merge_mode: int = EC_MERGE_MEAN, check=True) -> int:
+    """Ragged batch: k,v [B,H,T_max,D]; anchor_idx [B,G,n_max]; seq_len, n_anchor_b int32 [B] on the device."""
+    B, H, T, D = k.shape
+    G, n_max = anchor_idx.shape[1], anchor_idx.shape[2]
+    rc = load().ec_merge_compact_varlen(_ptr(k, "k"), _ptr(v, "v"), _ptr(anchor_idx, "anchor_idx"),
+                                        _i32(seq_len, "seq_len", B), _i32(n_anchor_b, "n_anchor_b", B), B, H, G, T, D,
+                                        n_max, dtype_code(k), merge_mode, _ptr(k_cache, "k_cache"),
+                                        _ptr(v_cache, "v_cache"), k_cache.shape[2], _ptr(counts, "counts"),
+                                        _ptr(assign, "assign"), _ptr(pos, "pos"), _stream())
+    if check and rc != EC_OK:
+        raise EcError("ec_merge_compact_varlen", rc)
+    return rc
+
+
+def ec_decode_step_varlen(q, k_new, v_new, k_cache, v_cache, pos, cache_len_b, evict_idx_b, new_pos_b, scale: float,
+                          out, G: int | None = None, check=True) -> int:
+    """Ragged batch: per-sequence cache length, victim and position as int32 [B] device tensors."""
+    B, H, cap, D = k_cache.shape
+    if G is None:
+        G = pos.shape[1] if pos is not None else 1
+    rc = load().ec_decode_step_varlen(_ptr(q, "q"), _ptr(k_new, "k_new"), _ptr(v_new, "v_new"), _ptr(k_cache, "k_cache"),
+                                      _ptr(v_cache, "v_cache"), _ptr(pos, "pos"), _i32(cache_len_b, "cache_len_b", B),
+                                      _i32(evict_idx_b, "evict_idx_b", B), _i32(new_pos_b, "new_pos_b", B), B, H, G, D,
+                                      cap, scale, dtype_code(k_cache), _ptr(out, "out"), None, 0, _stream())
+    if check and rc != EC_OK:
+        raise EcError("ec_decode_step_varlen", rc)
     return rc

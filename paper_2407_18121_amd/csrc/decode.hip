@@ -36,9 +36,16 @@ __global__ __launch_bounds__(WAVES * kWave) void decode_step_kernel(
     const uint4* __restrict__ q, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
     uint4* k_cache, uint4* v_cache, int32_t* pos, uint4* __restrict__ out, int H, int G, int cap,
     int cache_len, int evict_idx, int32_t new_pos, float scale_log2e, float* __restrict__ raw,
-    float* __restrict__ stats)
+    float* __restrict__ stats, const int32_t* __restrict__ len_b, const int32_t* __restrict__ evict_b,
+    const int32_t* __restrict__ new_pos_b)
 {
     using S = DecodeShape<DT, D, WAVES, UNROLL>;
+    if (len_b) {  // ragged batch: every batch element has its own cache length, victim and position
+        const int b = blockIdx.x / H;
+        cache_len = min(max(len_b[b], 0), cap - 1);
+        evict_idx = evict_b ? min(max(evict_b[b], -1), cache_len) : -1;
+        if (new_pos_b) new_pos = new_pos_b[b];
+    }
     constexpr int kDecodeUnroll = UNROLL;
     constexpr int LPR = S::kLPR, RPW = S::kRPW, EPL = S::kEPL, THREADS = S::kThreads, TILE = S::kTile;
     const int bh = blockIdx.x;
@@ -252,13 +259,14 @@ __global__ __launch_bounds__(WAVES * kWave) void decode_step_kernel(
 template <int DT, int D, int WAVES, int UNROLL>
 static int launch_decode_w(const void* q, const void* k_new, const void* v_new, void* k_cache,
                            void* v_cache, int32_t* pos, int B, int H, int G, int cap, int cache_len,
-                           int evict_idx, int32_t new_pos, float scale, void* out, hipStream_t stream)
+                           int evict_idx, int32_t new_pos, float scale, void* out, const int32_t* len_b,
+                           const int32_t* evict_b, const int32_t* new_pos_b, hipStream_t stream)
 {
     using S = DecodeShape<DT, D, WAVES, UNROLL>;
     hipLaunchKernelGGL((decode_step_kernel<DT, D, WAVES, UNROLL, false>), dim3(B * H), dim3(S::kThreads), 0, stream,
                        (const uint4*)q, (const uint4*)k_new, (const uint4*)v_new, (uint4*)k_cache,
                        (uint4*)v_cache, pos, (uint4*)out, H, G, cap, cache_len, evict_idx, new_pos,
-                       scale * kLog2e, (float*)nullptr, (float*)nullptr);
+                       scale * kLog2e, (float*)nullptr, (float*)nullptr, len_b, evict_b, new_pos_b);
     return status_from_hip(hipGetLastError());
 }
 
@@ -267,16 +275,17 @@ template <int DT, int D>
 static int launch_decode(const void* q, const void* k_new, const void* v_new, void* k_cache,
                          void* v_cache, int32_t* pos, int B, int H, int G, int cap, int cache_len,
                          int evict_idx, int32_t new_pos, float scale, void* out, int forced_waves,
-                         int forced_unroll, hipStream_t stream)
+                         int forced_unroll, const int32_t* len_b, const int32_t* evict_b, const int32_t* new_pos_b,
+                         hipStream_t stream)
 {
-    const int n_rows = cache_len + 1;
+    const int n_rows = cache_len + 1;  // ragged batches pass the longest length the buffers allow
     int waves = forced_waves, unroll = forced_unroll;
     if (waves <= 0) waves = (n_rows >= 96) ? 8 : 4;  // measured: 8 waves x 4 loads each beats 16 x 4 at every shape
     if (unroll <= 0) unroll = 4;
 #define EC_DECODE_W(W_, U_)                                                                              \
     if (waves == W_ && unroll == U_)                                                                     \
         return launch_decode_w<DT, D, W_, U_>(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, cap, cache_len, \
-                                              evict_idx, new_pos, scale, out, stream);
+                                              evict_idx, new_pos, scale, out, len_b, evict_b, new_pos_b, stream);
     EC_DECODE_W(4, 4)
     EC_DECODE_W(8, 4)
     EC_DECODE_W(16, 4)
@@ -291,13 +300,13 @@ static int launch_decode(const void* q, const void* k_new, const void* v_new, vo
 int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                     int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
                     int32_t new_pos, float scale, int dt, void* out, int forced_waves, int forced_unroll,
-                    hipStream_t stream)
+                    const int32_t* len_b, const int32_t* evict_b, const int32_t* new_pos_b, hipStream_t stream)
 {
 #define EC_DECODE_CASE(DT_, D_)                                                                       \
     if (dt == DT_ && D == D_)                                                                         \
         return launch_decode<DT_, D_>(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, cap, cache_len,    \
                                       evict_idx, new_pos, scale, out, forced_waves,       \
-                                      forced_unroll, stream);
+                                      forced_unroll, len_b, evict_b, new_pos_b, stream);
     EC_DECODE_CASE(EC_BF16, 128)
     EC_DECODE_CASE(EC_BF16, 64)
     EC_DECODE_CASE(EC_F32, 128)
@@ -343,7 +352,7 @@ static int launch_decode_score(const void* q, const void* k_new, const void* v_n
     hipLaunchKernelGGL((decode_step_kernel<DT, D, WAVES, 4, true>), dim3(B * H), dim3(S::kThreads), 0, stream,
                        (const uint4*)q, (const uint4*)k_new, (const uint4*)v_new, (uint4*)k_cache,
                        (uint4*)v_cache, pos, (uint4*)out, H, G, cap, cache_len, -1, new_pos, scale * kLog2e, raw,
-                       stats);
+                       stats, (const int32_t*)nullptr, (const int32_t*)nullptr, (const int32_t*)nullptr);
     int rc = status_from_hip(hipGetLastError());
     if (rc != EC_OK) return rc;
     const int n = cache_len + 1;

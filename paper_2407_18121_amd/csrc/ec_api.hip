@@ -8,7 +8,7 @@ namespace ec {
 int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                     int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
                     int32_t new_pos, float scale, int dt, void* out, int forced_waves, int forced_unroll,
-                    hipStream_t stream);
+                    const int32_t* len_b, const int32_t* evict_b, const int32_t* new_pos_b, hipStream_t stream);
 int decode_score_dispatch(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                           int32_t* pos, float* freq, int B, int H, int G, int D, int cap, int cache_len,
                           int32_t new_pos, float scale, int dt, void* out, float* raw, float* stats,
@@ -18,15 +18,16 @@ int evict_min_dispatch(void* k_cache, void* v_cache, int32_t* pos, float* freq, 
 int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, const int32_t* weights,
                    const int32_t* src_pos, int B, int H, int G, int T, int src_rows, int D, int n_anchor, int dt,
                    int evict_only, void* k_cache, void* v_cache, int cap, int32_t* counts, int32_t* assign,
-                   int32_t* pos, hipStream_t stream);
+                   int32_t* pos, const int32_t* seq_len, const int32_t* n_anchor_b, hipStream_t stream);
 int select_dispatch(const float* score, int B, int G, int T, int n_anchor, int protect_first,
-                    int protect_last, int32_t* anchor_idx, hipStream_t stream);
+                    int protect_last, int32_t* anchor_idx, const int32_t* seq_len, const int32_t* n_anchor_b,
+                    hipStream_t stream);
 int score_simt_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
-                        float* head_imp, int B, int H, ScoreGeom geo, int D, int dt, float scale,
-                        hipStream_t stream);
+                        float* head_imp, int B, int H, ScoreGeom geo, const int32_t* seq_len, int D, int dt,
+                        float scale, hipStream_t stream);
 int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
-                        float* head_imp, void* vt, int B, int H, ScoreGeom geo, int D, int dt, float scale,
-                        int forced_waves, hipStream_t stream);
+                        float* head_imp, void* vt, int B, int H, ScoreGeom geo, const int32_t* seq_len, int D,
+                        int dt, float scale, int forced_waves, hipStream_t stream);
 size_t score_mfma_vt_bytes(int B, int H, int T, int D);
 int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, hipStream_t stream);
 }  // namespace ec
@@ -46,7 +47,8 @@ int env_int(const char* name, int dflt)
 
 // Scoring pass of either entry point: Tq queries over L = P + Tq rows, heads of k/v kv_rows rows apart.
 int score_pass(const void* q, const void* k, const void* v, void* out, float* lse, float* score, int B, int H,
-               int G, ec::ScoreGeom geo, int D, int dt, float scale, void* ws, size_t ws_bytes, void* stream)
+               int G, ec::ScoreGeom geo, const int32_t* seq_len, int D, int dt, float scale, void* ws,
+               size_t ws_bytes, void* stream)
 {
     if (!q || !k || !v || !score) return EC_EINVAL;
     if (B < 1 || H < 1 || geo.Tq < 1 || geo.P < 0 || D < 1) return EC_EINVAL;
@@ -70,10 +72,10 @@ int score_pass(const void* q, const void* k, const void* v, void* out, float* ls
     int rc;
     const bool use_mfma = (dt == EC_BF16) && !env_int("EC_SCORE_FORCE_SIMT", 0);
     if (use_mfma)
-        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, ws_vt, B, H, geo, D, dt, scale,
+        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, ws_vt, B, H, geo, seq_len, D, dt, scale,
                                      env_int("EC_SCORE_WAVES", 0), s);
     else
-        rc = ec::score_simt_dispatch(q, k, v, out, lse_buf, head_imp, B, H, geo, D, dt, scale, s);
+        rc = ec::score_simt_dispatch(q, k, v, out, lse_buf, head_imp, B, H, geo, seq_len, D, dt, scale, s);
     if (rc != EC_OK) return rc;
     if (G == 1) rc = ec::head_mean_launch(head_imp, score, B, H, geo.L, s);
     return rc;
@@ -123,8 +125,17 @@ int ec_prefill_score(const void* q, const void* k, const void* v, void* out, flo
                      void* stream)
 {
     if (T < 1) return EC_EINVAL;
-    return score_pass(q, k, v, out, lse, score, B, H, G, ec::ScoreGeom{T, 0, T, T}, D, dt, scale, ws, ws_bytes,
-                      stream);
+    return score_pass(q, k, v, out, lse, score, B, H, G, ec::ScoreGeom{T, 0, T, T, T, T}, nullptr, D, dt, scale, ws,
+                      ws_bytes, stream);
+}
+
+int ec_prefill_score_varlen(const void* q, const void* k, const void* v, void* out, float* lse, float* score,
+                            const int32_t* seq_len, int B, int H, int G, int T_max, int D, int dt, float scale,
+                            void* ws, size_t ws_bytes, void* stream)
+{
+    if (T_max < 1 || !seq_len) return EC_EINVAL;
+    return score_pass(q, k, v, out, lse, score, B, H, G, ec::ScoreGeom{T_max, 0, T_max, T_max, T_max, T_max}, seq_len,
+                      D, dt, scale, ws, ws_bytes, stream);
 }
 
 int ec_chunk_score(const void* q, const void* k, const void* v, void* out, float* lse, float* score, int B,
@@ -132,8 +143,8 @@ int ec_chunk_score(const void* q, const void* k, const void* v, void* out, float
                    size_t ws_bytes, void* stream)
 {
     if (T_new < 1 || P < 0 || (long long)P + T_new > 0x7fffffffLL / 2) return EC_EINVAL;
-    return score_pass(q, k, v, out, lse, score, B, H, G, ec::ScoreGeom{T_new, P, P + T_new, kv_rows}, D, dt,
-                      scale, ws, ws_bytes, stream);
+    return score_pass(q, k, v, out, lse, score, B, H, G, ec::ScoreGeom{T_new, P, P + T_new, kv_rows, T_new, P + T_new},
+                      nullptr, D, dt, scale, ws, ws_bytes, stream);
 }
 
 int ec_select_anchors(const float* score, int B, int G, int T, int n_anchor, int protect_first,
@@ -146,8 +157,22 @@ int ec_select_anchors(const float* score, int B, int G, int T, int n_anchor, int
     if (protect_first < 0 || protect_last < 0) return EC_EINVAL;
     if ((long long)protect_first + protect_last > n_anchor) return EC_EINVAL;
     if (T > 65536) return EC_EUNSUPPORTED;
-    return ec::select_dispatch(score, B, G, T, n_anchor, protect_first, protect_last, anchor_idx,
+    return ec::select_dispatch(score, B, G, T, n_anchor, protect_first, protect_last, anchor_idx, nullptr, nullptr,
                                reinterpret_cast<hipStream_t>(stream));
+}
+
+int ec_select_anchors_varlen(const float* score, const int32_t* seq_len, const int32_t* n_anchor_b, int B, int G,
+                             int T_max, int n_max, int protect_first, int protect_last, int32_t* anchor_idx,
+                             void* ws, size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    if (!score || !anchor_idx || !seq_len || !n_anchor_b) return EC_EINVAL;
+    if (B < 1 || G < 1 || T_max < 1 || n_max < 1 || n_max > T_max) return EC_EINVAL;
+    if (protect_first < 0 || protect_last < 0) return EC_EINVAL;
+    if (T_max > 65536) return EC_EUNSUPPORTED;
+    return ec::select_dispatch(score, B, G, T_max, n_max, protect_first, protect_last, anchor_idx, seq_len,
+                               n_anchor_b, reinterpret_cast<hipStream_t>(stream));
 }
 
 int ec_merge_compact(const void* k, const void* v, const int32_t* anchor_idx, int B, int H, int G, int T,
@@ -172,8 +197,26 @@ int ec_remerge_compact(const void* k, const void* v, int src_rows, const int32_t
     if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
     if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
     return ec::merge_dispatch(k, v, anchor_idx, weights, src_pos, B, H, G, L, src_rows, D, n_anchor, dt,
-                              merge_mode == EC_MERGE_EVICT, k_cache, v_cache, cap, counts, assign, pos,
-                              reinterpret_cast<hipStream_t>(stream));
+                              merge_mode == EC_MERGE_EVICT, k_cache, v_cache, cap, counts, assign, pos, nullptr,
+                              nullptr, reinterpret_cast<hipStream_t>(stream));
+}
+
+int ec_merge_compact_varlen(const void* k, const void* v, const int32_t* anchor_idx, const int32_t* seq_len,
+                            const int32_t* n_anchor_b, int B, int H, int G, int T_max, int D, int n_max, int dt,
+                            int merge_mode, void* k_cache, void* v_cache, int cap, int32_t* counts,
+                            int32_t* assign, int32_t* pos, void* stream)
+{
+    if (merge_mode != EC_MERGE_MEAN && merge_mode != EC_MERGE_EVICT) return EC_EINVAL;
+    if (!k || !v || !anchor_idx || !k_cache || !v_cache || !seq_len || !n_anchor_b) return EC_EINVAL;
+    if (k == k_cache || v == v_cache || k == v_cache || v == k_cache) return EC_EINVAL;
+    if (B < 1 || H < 1 || T_max < 1 || D < 1 || cap < 1) return EC_EINVAL;
+    if (G != 1 && G != H) return EC_EINVAL;
+    if (n_max < 1 || n_max > T_max || n_max > cap) return EC_EINVAL;
+    if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
+    if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
+    return ec::merge_dispatch(k, v, anchor_idx, nullptr, nullptr, B, H, G, T_max, T_max, D, n_max, dt,
+                              merge_mode == EC_MERGE_EVICT, k_cache, v_cache, cap, counts, assign, pos, seq_len,
+                              n_anchor_b, reinterpret_cast<hipStream_t>(stream));
 }
 
 int ec_evict_index(int64_t n_seen, int len_after_append, int gamma_num, int gamma_den, int budget_mode,
@@ -221,7 +264,27 @@ int ec_decode_step(const void* q, const void* k_new, const void* v_new, void* k_
     (void)ws_bytes;
     return ec::decode_dispatch(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, D, cap, cache_len, evict_idx,
                                new_pos, scale, dt, out, env_int("EC_DECODE_WAVES", 0), env_int("EC_DECODE_UNROLL", 0),
-                               reinterpret_cast<hipStream_t>(stream));
+                               nullptr, nullptr, nullptr, reinterpret_cast<hipStream_t>(stream));
+}
+
+int ec_decode_step_varlen(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                          int32_t* pos, const int32_t* cache_len_b, const int32_t* evict_idx_b,
+                          const int32_t* new_pos_b, int B, int H, int G, int D, int cap, float scale, int dt,
+                          void* out, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!q || !k_new || !v_new || !k_cache || !v_cache || !out || !cache_len_b) return EC_EINVAL;
+    if (B < 1 || H < 1 || D < 1 || cap < 1) return EC_EINVAL;
+    if (G != 1 && G != H) return EC_EINVAL;
+    if (pos && !new_pos_b) return EC_EINVAL;
+    if (!(scale == scale)) return EC_EINVAL;
+    if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
+    if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
+    (void)ws;
+    (void)ws_bytes;
+    // the lengths live on the device: the launch shape is chosen for the longest cache the buffers allow
+    return ec::decode_dispatch(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, D, cap, cap - 1, -1, 0, scale, dt, out,
+                               env_int("EC_DECODE_WAVES", 0), env_int("EC_DECODE_UNROLL", 0), cache_len_b, evict_idx_b,
+                               new_pos_b, reinterpret_cast<hipStream_t>(stream));
 }
 
 int ec_decode_score_step(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,

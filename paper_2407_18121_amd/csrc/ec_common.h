@@ -119,9 +119,17 @@ __device__ __forceinline__ float wave_max(float x)
 // Geometry of one scoring pass.  Every head of k/v holds P rows of an existing compressed cache followed
 // by the Tq rows of the chunk being encoded (L = P + Tq rows), heads kv_rows rows apart.  Query m of the
 // chunk sees rows n <= P + m.  The first-turn pass over a bare prompt is P = 0, kv_rows = Tq.
+// q, out and the row log-sum-exp have q_rows rows per head, the per-head importance imp_rows.  For a ragged
+// batch (P = 0) Tq is the padded length all strides are built on and batch element b has seq_len[b] rows.
 struct ScoreGeom {
-    int Tq, P, L, kv_rows;
+    int Tq, P, L, kv_rows, q_rows, imp_rows;
 };
+
+// Rows of batch element b in a ragged batch (clamped into [0, t_max]); t_max for a dense one.
+__device__ __forceinline__ int ragged_rows(const int32_t* __restrict__ seq_len, int b, int t_max)
+{
+    return seq_len ? min(max(seq_len[b], 0), t_max) : t_max;
+}
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;

@@ -36,8 +36,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     const uint4* __restrict__ k, const uint4* __restrict__ v, const int32_t* __restrict__ anchor_idx,
     const int32_t* __restrict__ weights, const int32_t* __restrict__ src_pos,
     uint4* __restrict__ k_cache, uint4* __restrict__ v_cache, int32_t* __restrict__ counts,
-    int32_t* __restrict__ assign, int32_t* __restrict__ pos, int H, int G, int T, int src_rows, int n_anchor,
-    int cap, int evict_only)
+    int32_t* __restrict__ assign, int32_t* __restrict__ pos, int H, int G, int T_max, int src_rows, int n_max,
+    int cap, int evict_only, const int32_t* __restrict__ seq_len, const int32_t* __restrict__ n_anchor_b)
 {
     constexpr int LPR = D * Elem<DT>::kBytes / 16;
     constexpr int EPL = Elem<DT>::kPerChunk;
@@ -50,11 +50,14 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     // from piling onto the same XCDs.
     const int chunk = (blockIdx.x + blockIdx.y) % gridDim.x;
     const int j = chunk * GROUPS + threadIdx.x / LPR;
+    // ragged batches: batch element b has T positions and n_anchor anchors; array rows stay T_max / n_max apart
+    const int T = ragged_rows(seq_len, b, T_max);
+    const int n_anchor = n_anchor_b ? min(max(n_anchor_b[b], 0), min(T, n_max)) : n_max;
     if (j >= n_anchor) return;
 
     const size_t bg = (size_t)b * G + (G == 1 ? 0 : h);
-    const int32_t* a = anchor_idx + bg * n_anchor;
-    const int32_t* wrow = WEIGHTED ? weights + bg * T : nullptr;
+    const int32_t* a = anchor_idx + bg * n_max;
+    const int32_t* wrow = WEIGHTED ? weights + bg * T_max : nullptr;
     int lo, hi;
     bucket_bounds(a, j, n_anchor, T, lo, hi);
     const int blo = lo, bhi = hi;  // the bucket, for the bookkeeping
@@ -125,14 +128,14 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     // bookkeeping, once per score group: bucket size, position of the cache row, bucket of every position
     if (G == H || h == 0) {
         if (sub == 0) {
-            if (counts) counts[bg * n_anchor + j] = count;
+            if (counts) counts[bg * n_max + j] = count;
             if (pos) {
                 const int t = min(max(a[j], 0), T - 1);
-                pos[bg * cap + j] = src_pos ? src_pos[bg * T + t] : a[j];
+                pos[bg * cap + j] = src_pos ? src_pos[bg * T_max + t] : a[j];
             }
         }
         if (assign)
-            for (int t = blo + sub; t <= bhi; t += LPR) assign[bg * T + t] = (!evict_only || t == lo) ? j : -1;
+            for (int t = blo + sub; t <= bhi; t += LPR) assign[bg * T_max + t] = (!evict_only || t == lo) ? j : -1;
     }
 }
 
@@ -140,7 +143,7 @@ template <int DT, int D>
 static int launch_merge(const void* k, const void* v, const int32_t* anchor_idx, const int32_t* weights,
                         const int32_t* src_pos, int B, int H, int G, int T, int src_rows, int n_anchor, void* k_cache,
                         void* v_cache, int cap, int32_t* counts, int32_t* assign, int32_t* pos, int evict_only,
-                        hipStream_t stream)
+                        const int32_t* seq_len, const int32_t* n_anchor_b, hipStream_t stream)
 {
     constexpr int LPR = D * Elem<DT>::kBytes / 16;
     constexpr int GROUPS = kMergeThreads / LPR;
@@ -148,23 +151,25 @@ static int launch_merge(const void* k, const void* v, const int32_t* anchor_idx,
     if (weights != nullptr && !evict_only)
         hipLaunchKernelGGL((merge_compact_kernel<DT, D, true>), grid, dim3(kMergeThreads), 0, stream,
                            (const uint4*)k, (const uint4*)v, anchor_idx, weights, src_pos, (uint4*)k_cache,
-                           (uint4*)v_cache, counts, assign, pos, H, G, T, src_rows, n_anchor, cap, evict_only);
+                           (uint4*)v_cache, counts, assign, pos, H, G, T, src_rows, n_anchor, cap, evict_only, seq_len,
+                           n_anchor_b);
     else
         hipLaunchKernelGGL((merge_compact_kernel<DT, D, false>), grid, dim3(kMergeThreads), 0, stream,
                            (const uint4*)k, (const uint4*)v, anchor_idx, weights, src_pos, (uint4*)k_cache,
-                           (uint4*)v_cache, counts, assign, pos, H, G, T, src_rows, n_anchor, cap, evict_only);
+                           (uint4*)v_cache, counts, assign, pos, H, G, T, src_rows, n_anchor, cap, evict_only, seq_len,
+                           n_anchor_b);
     return status_from_hip(hipGetLastError());
 }
 
 int merge_dispatch(const void* k, const void* v, const int32_t* anchor_idx, const int32_t* weights,
                    const int32_t* src_pos, int B, int H, int G, int T, int src_rows, int D, int n_anchor, int dt,
                    int evict_only, void* k_cache, void* v_cache, int cap, int32_t* counts, int32_t* assign,
-                   int32_t* pos, hipStream_t stream)
+                   int32_t* pos, const int32_t* seq_len, const int32_t* n_anchor_b, hipStream_t stream)
 {
 #define EC_MERGE_CASE(DT_, D_)                                                                               \
     if (dt == DT_ && D == D_)                                                                                \
         return launch_merge<DT_, D_>(k, v, anchor_idx, weights, src_pos, B, H, G, T, src_rows, n_anchor, k_cache, \
-                                     v_cache, cap, counts, assign, pos, evict_only, stream);
+                                     v_cache, cap, counts, assign, pos, evict_only, seq_len, n_anchor_b, stream);
     EC_MERGE_CASE(EC_BF16, 128)
     EC_MERGE_CASE(EC_BF16, 64)
     EC_MERGE_CASE(EC_F32, 128)

@@ -53,11 +53,12 @@ __device__ __forceinline__ int xcd_contiguous_item(int linear_id, int total)
 
 // ------------------------------------------------------------------ V^T
 __global__ __launch_bounds__(256) void vt_transpose_kernel(const uint16_t* __restrict__ v,
-                                                           uint16_t* __restrict__ vt, int T, int Tp, int D,
-                                                           int kv_rows)
+                                                           uint16_t* __restrict__ vt, int T_max, int Tp, int D,
+                                                           int kv_rows, const int32_t* __restrict__ seq_len, int H)
 {
     __shared__ uint16_t tile[64][64 + 2];
     const int bh = blockIdx.z;
+    const int T = ragged_rows(seq_len, bh / H, T_max);  // rows beyond it are written as zeros
     const int n0 = blockIdx.x * 64, d0 = blockIdx.y * 64;
     const uint16_t* src = v + (size_t)bh * kv_rows * D;
     uint16_t* dst = vt + (size_t)bh * D * Tp;
@@ -84,9 +85,8 @@ template <int D, int WAVES>
 __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     uint16_t* __restrict__ out, float* __restrict__ lse, ScoreGeom geo, int Tp, float scale_log2e, int n_qtiles,
-    int n_heads)
+    int n_heads, const int32_t* __restrict__ seq_len, int H)
 {
-    const int Tq = geo.Tq, P = geo.P, L = geo.L;
     constexpr int THREADS = WAVES * kWave;
     constexpr int BM = WAVES * 32;   // queries per workgroup
     constexpr int KB = D / 16;       // contraction blocks of Q.K
@@ -107,10 +107,12 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     const int item = xcd_contiguous_item(blockIdx.x, n_qtiles * n_heads);
     if (item >= n_qtiles * n_heads) return;
     const int bh = item / n_qtiles;
+    const int Tq = ragged_rows(seq_len, bh / H, geo.Tq), P = geo.P, L = P + Tq;
     const int m0 = (n_qtiles - 1 - item % n_qtiles) * BM;  // longest rows first inside a head
+    if (m0 >= Tq) return;  // ragged batch: this sequence ends before the tile (whole workgroup)
     const int mw = m0 + wave * 32;                          // first query of this wave
     const int m = mw + c32;                            // this lane's query
-    const uint16_t* qh = q + (size_t)bh * Tq * D;
+    const uint16_t* qh = q + (size_t)bh * geo.q_rows * D;
     const uint16_t* kh = k + (size_t)bh * geo.kv_rows * D;
     const uint16_t* vth = vt + (size_t)bh * D * Tp;
     const bool want_out = out != nullptr;
@@ -275,10 +277,10 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     if (m < Tq) {
-        if (h == 0) lse[(size_t)bh * Tq + m] = (m_run + log2f(l_tot)) * kLn2;
+        if (h == 0) lse[(size_t)bh * geo.q_rows + m] = (m_run + log2f(l_tot)) * kLn2;
         if (want_out) {
             const float inv = 1.f / l_tot;
-            uint16_t* orow = out + ((size_t)bh * Tq + m) * D;
+            uint16_t* orow = out + ((size_t)bh * geo.q_rows + m) * D;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -296,11 +298,11 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 template <int D>
 __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const float* __restrict__ lse,
-    float* __restrict__ head_imp, ScoreGeom geo, float scale_log2e, int n_ktiles, int n_heads)
+    float* __restrict__ head_imp, ScoreGeom geo, float scale_log2e, int n_ktiles, int n_heads,
+    const int32_t* __restrict__ seq_len, int H)
 {
     constexpr int KB = D / 16;
     constexpr int QP = D + 8;
-    const int Tq = geo.Tq, P = geo.P, L = geo.L;
     __shared__ __align__(16) uint16_t qs[2][kColBM * QP];
     __shared__ __align__(16) float lse2[2][kColBM];  // row log-sum-exp in base-2 units
 
@@ -309,11 +311,13 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
     const int item = xcd_contiguous_item(blockIdx.x, n_ktiles * n_heads);
     if (item >= n_ktiles * n_heads) return;
     const int bh = item / n_ktiles;
+    const int Tq = ragged_rows(seq_len, bh / H, geo.Tq), P = geo.P, L = P + Tq;
     const int n0 = (item % n_ktiles) * kColBN;  // low key tiles (most query tiles) first inside a head
+    if (n0 >= L) return;  // ragged batch: this sequence ends before the tile (whole workgroup)
     const int n = n0 + wave * 32 + c32;  // this lane's key
-    const uint16_t* qh = q + (size_t)bh * Tq * D;
+    const uint16_t* qh = q + (size_t)bh * geo.q_rows * D;
     const uint16_t* kh = k + (size_t)bh * geo.kv_rows * D;
-    const float* lh = lse + (size_t)bh * Tq;
+    const float* lh = lse + (size_t)bh * geo.q_rows;
 
     bf16x8 kf[KB];
 #pragma unroll
@@ -425,13 +429,13 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
         __syncthreads();
     }
     col += __shfl_xor(col, 32, kWave);
-    if (h == 0 && n < L) head_imp[(size_t)bh * L + n] = col;
+    if (h == 0 && n < L) head_imp[(size_t)bh * geo.imp_rows + n] = col;
 }
 
 template <int D>
 static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse,
-                       float* head_imp, uint16_t* vt, int B, int H, ScoreGeom geo, float scale, int forced_waves,
-                       hipStream_t stream)
+                       float* head_imp, uint16_t* vt, int B, int H, ScoreGeom geo, const int32_t* seq_len, float scale,
+                       int forced_waves, hipStream_t stream)
 {
     const float sl = scale * kLog2e;
     const int Tq = geo.Tq, L = geo.L;
@@ -439,7 +443,7 @@ static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, 
     const int BH = B * H;
     if (out != nullptr) {
         hipLaunchKernelGGL(vt_transpose_kernel, dim3(Lp / 64, D / 64, BH), dim3(256), 0, stream, v, vt, L, Lp, D,
-                           geo.kv_rows);
+                           geo.kv_rows, seq_len, H);
         int rc = status_from_hip(hipGetLastError());
         if (rc != EC_OK) return rc;
     }
@@ -449,14 +453,15 @@ static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, 
     if (waves != 4 && waves != 8) waves = ((long long)BH * ((Tq + 255) / 256) >= 512) ? 8 : 4;
     if (waves == 8)
         hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 8>), dim3(xcd_grid(((Tq + 255) / 256) * BH)), dim3(512), 0,
-                           stream, q, k, vt, out, lse, geo, Lp, sl, (Tq + 255) / 256, BH);
+                           stream, q, k, vt, out, lse, geo, Lp, sl, (Tq + 255) / 256, BH, seq_len, H);
     else
         hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 4>), dim3(xcd_grid(((Tq + 127) / 128) * BH)), dim3(256), 0,
-                           stream, q, k, vt, out, lse, geo, Lp, sl, (Tq + 127) / 128, BH);
+                           stream, q, k, vt, out, lse, geo, Lp, sl, (Tq + 127) / 128, BH, seq_len, H);
     int rc = status_from_hip(hipGetLastError());
     if (rc != EC_OK) return rc;
     hipLaunchKernelGGL((colsum_mfma_kernel<D>), dim3(xcd_grid(((L + kColBN - 1) / kColBN) * BH)),
-                       dim3(kMfmaThreads), 0, stream, q, k, lse, head_imp, geo, sl, (L + kColBN - 1) / kColBN, BH);
+                       dim3(kMfmaThreads), 0, stream, q, k, lse, head_imp, geo, sl, (L + kColBN - 1) / kColBN, BH,
+                       seq_len, H);
     return status_from_hip(hipGetLastError());
 }
 
@@ -465,16 +470,16 @@ size_t score_mfma_vt_bytes(int B, int H, int T, int D) { return (size_t)B * H * 
 
 // Per-head importance into head_imp [B,H,L]; out may be NULL (then vt is not touched).
 int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse, float* head_imp,
-                        void* vt, int B, int H, ScoreGeom geo, int D, int dt, float scale, int forced_waves,
-                        hipStream_t stream)
+                        void* vt, int B, int H, ScoreGeom geo, const int32_t* seq_len, int D, int dt, float scale,
+                        int forced_waves, hipStream_t stream)
 {
     if (dt != EC_BF16) return EC_EUNSUPPORTED;
     if (D == 128)
         return launch_mfma<128>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out, lse,
-                                head_imp, (uint16_t*)vt, B, H, geo, scale, forced_waves, stream);
+                                head_imp, (uint16_t*)vt, B, H, geo, seq_len, scale, forced_waves, stream);
     if (D == 64)
         return launch_mfma<64>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out, lse,
-                               head_imp, (uint16_t*)vt, B, H, geo, scale, forced_waves, stream);
+                               head_imp, (uint16_t*)vt, B, H, geo, seq_len, scale, forced_waves, stream);
     return EC_EUNSUPPORTED;
 }
 

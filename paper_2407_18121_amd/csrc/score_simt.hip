@@ -90,10 +90,11 @@ __device__ __forceinline__ float row16_max(float x)
 template <int DT, int D>
 __global__ __launch_bounds__(kSimtThreads) void attn_fwd_simt_kernel(
     const void* __restrict__ q, const void* __restrict__ k, const void* __restrict__ v,
-    void* __restrict__ out, float* __restrict__ lse, ScoreGeom geo, float scale_log2e)
+    void* __restrict__ out, float* __restrict__ lse, ScoreGeom geo, float scale_log2e,
+    const int32_t* __restrict__ seq_len, int H)
 {
     constexpr int CPT = D / 16;  // output columns per thread
-    const int Tq = geo.Tq, P = geo.P, L = geo.L;
+    const int Tq = ragged_rows(seq_len, blockIdx.y / H, geo.Tq), P = geo.P, L = P + Tq;
     __shared__ SimtSmem sm;
     __shared__ float ps[kBM][kBN + 1];
     __shared__ __align__(16) float vs[kBN][D];
@@ -101,8 +102,9 @@ __global__ __launch_bounds__(kSimtThreads) void attn_fwd_simt_kernel(
     const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
     const int bh = blockIdx.y;
     const int m0 = (gridDim.x - 1 - blockIdx.x) * kBM;  // longest rows first
+    if (m0 >= Tq) return;  // ragged batch: this sequence ends before the tile (whole workgroup)
     using E = typename Elem<DT>::type;
-    const E* qh = reinterpret_cast<const E*>(q) + (size_t)bh * Tq * D;
+    const E* qh = reinterpret_cast<const E*>(q) + (size_t)bh * geo.q_rows * D;
     const E* kh = reinterpret_cast<const E*>(k) + (size_t)bh * geo.kv_rows * D;
     const E* vh = reinterpret_cast<const E*>(v) + (size_t)bh * geo.kv_rows * D;
 
@@ -175,10 +177,10 @@ __global__ __launch_bounds__(kSimtThreads) void attn_fwd_simt_kernel(
     for (int i = 0; i < 4; ++i) {
         const int m = m0 + ty * 4 + i;
         if (m >= Tq) continue;
-        if (tx == 0) lse[(size_t)bh * Tq + m] = (m_run[i] + log2f(l_run[i])) * kLn2;
+        if (tx == 0) lse[(size_t)bh * geo.q_rows + m] = (m_run[i] + log2f(l_run[i])) * kLn2;
         if (out != nullptr) {
             const float inv = 1.f / l_run[i];
-            E* orow = reinterpret_cast<E*>(out) + ((size_t)bh * Tq + m) * D + tx * CPT;
+            E* orow = reinterpret_cast<E*>(out) + ((size_t)bh * geo.q_rows + m) * D + tx * CPT;
 #pragma unroll
             for (int c = 0; c < CPT; ++c) {
                 const float r = o[i][c] * inv;
@@ -194,19 +196,20 @@ __global__ __launch_bounds__(kSimtThreads) void attn_fwd_simt_kernel(
 template <int DT, int D>
 __global__ __launch_bounds__(kSimtThreads) void colsum_simt_kernel(
     const void* __restrict__ q, const void* __restrict__ k, const float* __restrict__ lse,
-    float* __restrict__ head_imp, ScoreGeom geo, float scale_log2e)
+    float* __restrict__ head_imp, ScoreGeom geo, float scale_log2e, const int32_t* __restrict__ seq_len, int H)
 {
     __shared__ SimtSmem sm;
     __shared__ float red[16][kBN];
-    const int Tq = geo.Tq, P = geo.P, L = geo.L;
+    const int Tq = ragged_rows(seq_len, blockIdx.y / H, geo.Tq), P = geo.P, L = P + Tq;
 
     const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
     const int bh = blockIdx.y;
     const int n0 = blockIdx.x * kBN;  // low key tiles (most query tiles) are scheduled first
+    if (n0 >= L) return;  // ragged batch: this sequence ends before the tile (whole workgroup)
     using E = typename Elem<DT>::type;
-    const E* qh = reinterpret_cast<const E*>(q) + (size_t)bh * Tq * D;
+    const E* qh = reinterpret_cast<const E*>(q) + (size_t)bh * geo.q_rows * D;
     const E* kh = reinterpret_cast<const E*>(k) + (size_t)bh * geo.kv_rows * D;
-    const float* lh = lse + (size_t)bh * Tq;
+    const float* lh = lse + (size_t)bh * geo.q_rows;
 
     float col[2] = {0.f, 0.f};
     for (int m0 = (max(n0 - P, 0) / kBM) * kBM; m0 < Tq; m0 += kBM) {  // query m sees keys n <= P + m
@@ -231,7 +234,7 @@ __global__ __launch_bounds__(kSimtThreads) void colsum_simt_kernel(
         float acc = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc += red[r][tid];
-        head_imp[(size_t)bh * L + n0 + tid] = acc;
+        head_imp[(size_t)bh * geo.imp_rows + n0 + tid] = acc;
     }
 }
 
@@ -264,28 +267,29 @@ int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, h
 
 template <int DT, int D>
 static int launch_simt(const void* q, const void* k, const void* v, void* out, float* lse,
-                       float* head_imp, int B, int H, ScoreGeom geo, float scale, hipStream_t stream)
+                       float* head_imp, int B, int H, ScoreGeom geo, const int32_t* seq_len, float scale,
+                       hipStream_t stream)
 {
     const float sl = scale * kLog2e;
     dim3 g1((geo.Tq + kBM - 1) / kBM, B * H);
     hipLaunchKernelGGL((attn_fwd_simt_kernel<DT, D>), g1, dim3(kSimtThreads), 0, stream, q, k, v, out, lse,
-                       geo, sl);
+                       geo, sl, seq_len, H);
     int rc = status_from_hip(hipGetLastError());
     if (rc != EC_OK) return rc;
     dim3 g2((geo.L + kBN - 1) / kBN, B * H);
     hipLaunchKernelGGL((colsum_simt_kernel<DT, D>), g2, dim3(kSimtThreads), 0, stream, q, k, lse, head_imp,
-                       geo, sl);
+                       geo, sl, seq_len, H);
     return status_from_hip(hipGetLastError());
 }
 
 // Per-head importance into head_imp [B,H,L]; out may be NULL.
 int score_simt_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
-                        float* head_imp, int B, int H, ScoreGeom geo, int D, int dt, float scale,
-                        hipStream_t stream)
+                        float* head_imp, int B, int H, ScoreGeom geo, const int32_t* seq_len, int D, int dt,
+                        float scale, hipStream_t stream)
 {
 #define EC_SIMT_CASE(DT_, D_)                                                                     \
     if (dt == DT_ && D == D_)                                                                     \
-        return launch_simt<DT_, D_>(q, k, v, out, lse, head_imp, B, H, geo, scale, stream);
+        return launch_simt<DT_, D_>(q, k, v, out, lse, head_imp, B, H, geo, seq_len, scale, stream);
     EC_SIMT_CASE(EC_F32, 64)
     EC_SIMT_CASE(EC_F32, 128)
     EC_SIMT_CASE(EC_BF16, 64)

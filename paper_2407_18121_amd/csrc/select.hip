@@ -44,9 +44,12 @@ __device__ __forceinline__ int block_excl_scan_flag(bool flag, int* wave_tot /*[
     return before + in_wave;
 }
 
+// Ragged batches: seq_len[b] positions and n_anchor_b[b] anchors for batch element b (both clamped), rows
+// of score and anchor_idx stay T_max and n_max apart.
 __global__ __launch_bounds__(kSelThreads) void select_anchors_kernel(
-    const float* __restrict__ score, int T, int n_anchor, int protect_first, int protect_last,
-    int32_t* __restrict__ anchor_idx, int keys_in_lds)
+    const float* __restrict__ score, int T_max, int n_max, int protect_first, int protect_last,
+    int32_t* __restrict__ anchor_idx, int keys_in_lds, const int32_t* __restrict__ seq_len,
+    const int32_t* __restrict__ n_anchor_b, int G)
 {
     extern __shared__ uint32_t lds_keys[];
     __shared__ int hist[256];
@@ -56,8 +59,14 @@ __global__ __launch_bounds__(kSelThreads) void select_anchors_kernel(
     __shared__ int sh_need;
 
     const int tid = threadIdx.x;
-    const float* s = score + (size_t)blockIdx.x * T;
-    int32_t* dst = anchor_idx + (size_t)blockIdx.x * n_anchor;
+    const int b = blockIdx.x / G;
+    const int T = ragged_rows(seq_len, b, T_max);
+    const int n_anchor = n_anchor_b ? min(max(n_anchor_b[b], 0), min(T, n_max)) : n_max;
+    if (T == 0 || n_anchor == 0) return;  // whole workgroup
+    protect_first = min(protect_first, n_anchor);
+    protect_last = min(protect_last, n_anchor - protect_first);
+    const float* s = score + (size_t)blockIdx.x * T_max;
+    int32_t* dst = anchor_idx + (size_t)blockIdx.x * n_max;
     const int free_lo = protect_first, free_hi = T - protect_last;  // unprotected: [free_lo, free_hi)
     const int n_free = n_anchor - protect_first - protect_last;
 
@@ -130,12 +139,13 @@ __global__ __launch_bounds__(kSelThreads) void select_anchors_kernel(
 }
 
 int select_dispatch(const float* score, int B, int G, int T, int n_anchor, int protect_first,
-                    int protect_last, int32_t* anchor_idx, hipStream_t stream)
+                    int protect_last, int32_t* anchor_idx, const int32_t* seq_len, const int32_t* n_anchor_b,
+                    hipStream_t stream)
 {
     const int keys_in_lds = T <= kSelLdsKeys;
     const size_t dyn = keys_in_lds ? (size_t)T * sizeof(uint32_t) : 0;
     hipLaunchKernelGGL(select_anchors_kernel, dim3(B * G), dim3(kSelThreads), dyn, stream, score, T,
-                       n_anchor, protect_first, protect_last, anchor_idx, keys_in_lds);
+                       n_anchor, protect_first, protect_last, anchor_idx, keys_in_lds, seq_len, n_anchor_b, G);
     return status_from_hip(hipGetLastError());
 }
 

@@ -57,6 +57,17 @@ def test_invalid_arguments_are_rejected_before_any_launch():
     assert lib.ec_chunk_score(one, one, one, None, None, one, 1, 1, 1, 0, 4, 12, 64, 0, 1.0, one, 1 << 20, None) == ec.EC_EINVAL  # empty chunk
     assert lib.ec_chunk_score(one, one, one, None, None, one, 1, 1, 1, 8, -1, 12, 64, 0, 1.0, one, 1 << 20, None) == ec.EC_EINVAL  # negative prefix
     assert lib.ec_chunk_score(one, one, one, None, None, one, 1, 1, 1, 8, 4, 12, 64, 0, 1.0, one, 16, None) == ec.EC_EWORKSPACE
+    # ragged-batch and frequency-policy entry points
+    assert lib.ec_prefill_score_varlen(one, one, one, None, None, one, None, 1, 1, 1, 8, 64, 0, 1.0, one, 1 << 20, None) == ec.EC_EINVAL  # no seq_len
+    assert lib.ec_select_anchors_varlen(one, one, None, 1, 1, 8, 4, 1, 1, one, None, 0, None) == ec.EC_EINVAL
+    assert lib.ec_select_anchors_varlen(one, one, one, 1, 1, 8, 9, 1, 1, one, None, 0, None) == ec.EC_EINVAL  # n_max > T_max
+    assert lib.ec_merge_compact_varlen(one, one, one, one, None, 1, 1, 1, 8, 64, 4, 0, 0, two, two, 4, None, None, None, None) == ec.EC_EINVAL
+    assert lib.ec_decode_step_varlen(one, one, one, one, one, None, None, None, None, 1, 1, 1, 64, 8, 1.0, 0, one, None, 0, None) == ec.EC_EINVAL
+    assert lib.ec_decode_step_varlen(one, one, one, one, one, one, one, None, None, 1, 1, 1, 64, 8, 1.0, 0, one, None, 0, None) == ec.EC_EINVAL  # pos without new_pos_b
+    assert lib.ec_decode_score_step(one, one, one, one, one, None, None, 1, 1, 1, 64, 8, 3, 0, 1.0, 0, one, one, 1 << 20, None) == ec.EC_EINVAL  # no freq
+    assert lib.ec_decode_score_step(one, one, one, one, one, None, one, 1, 1, 1, 64, 8, 3, 0, 1.0, 0, one, one, 16, None) == ec.EC_EWORKSPACE
+    assert lib.ec_evict_min(one, one, None, one, 1, 1, 1, 64, 8, 3, 2, 1, 0, one, None) == ec.EC_EINVAL   # nothing left to choose from
+    assert lib.ec_evict_min(one, one, None, one, 1, 1, 1, 64, 8, 9, 1, 1, 0, one, None) == ec.EC_EINVAL   # len > cap
 
 
 def test_evict_index_matches_oracle_everywhere():
