@@ -10,7 +10,9 @@ resident in HBM before the timed region.  Prints ONE JSON line.
 After the timed region it also times, outside `value`, a second turn (`detail.turn2`): a new chunk of
 `--turn2` tokens (default: half the prompt) is encoded over the cache the generation left behind with
 ec_chunk_score -> ec_select_anchors -> ec_remerge_compact; and `--freq-steps` generated tokens under the
-"Frequency" discard policy (`detail.frequency_policy`: ec_decode_score_step + ec_evict_min per layer-step).
+"Frequency" discard policy (`detail.frequency_policy`: ec_decode_score_step + ec_evict_min per layer-step); and, for
+batches of two or more, `--ragged-steps` tokens of a mixed-length batch through ec_decode_step_varlen
+(`detail.ragged_decode`).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--score-mode layer|head]
                     [--no-graph] [--no-cpu-baseline] [--turn2 N]
@@ -51,6 +53,8 @@ def parse():
                     help="tokens of the second-turn chunk timed after the main step (-1 = half the prompt, 0 = skip)")
     ap.add_argument("--freq-steps", type=int, default=32,
                     help="generated tokens timed under the frequency discard policy after the main step (0 = skip)")
+    ap.add_argument("--ragged-steps", type=int, default=16,
+                    help="generated tokens timed through ec_decode_step_varlen on a mixed-length batch (0 = skip; needs B >= 2)")
     ap.add_argument("--distinct-layers", type=int, default=0,
                     help="distinct prompt tensors to generate (0 = one per layer; fewer are cycled)")
     return ap.parse_args()
@@ -261,6 +265,37 @@ class FrequencyDecode:
             assert rc == 0, rc
 
 
+class RaggedDecode:
+    """ec_decode_step_varlen on a batch whose caches hold between half and all of the rows the main step ends
+    with (evenly spread), every sequence evicting at its own recent-distance location so that lengths stay put."""
+
+    def __init__(self, wl, steps):
+        import torch
+        cfg = wl.cfg
+        self.wl, self.lib = wl, wl.lib
+        B, H, D, L, G, cap = cfg.B, cfg.H, cfg.D, cfg.layers, wl.G, cfg.cap
+        N = min(wl.final_len, cap - 1)
+        lens = [N // 2 + (N - N // 2) * b // max(B - 1, 1) for b in range(B)]
+        self.lens, self.steps = lens, min(steps, cfg.decode_steps)
+        self.len_b = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        self.vic_b = torch.tensor([max(n - 25, 1) for n in lens], dtype=torch.int32, device="cuda")
+        self.pos_b = torch.tensor([cfg.T + 7] * B, dtype=torch.int32, device="cuda")
+        self.calls = []
+        for step in range(self.steps):
+            for l in range(L):
+                dq, dk, dv = wl.dec[l]
+                self.calls.append((dq[step].data_ptr(), dk[step].data_ptr(), dv[step].data_ptr(), wl.k_cache[l].data_ptr(),
+                                   wl.v_cache[l].data_ptr(), wl.pos[l].data_ptr(), self.len_b.data_ptr(), self.vic_b.data_ptr(),
+                                   self.pos_b.data_ptr(), B, H, G, D, cap, cfg.scale, wl.dt_code, wl.dec_out.data_ptr(), None, 0))
+        self.bytes_per_launch = sum(2.0 * H * (n + 1) * D * cfg.esize for n in lens)
+
+    def run(self, s):
+        f = self.lib.ec_decode_step_varlen
+        for a in self.calls:
+            rc = f(*a, s)
+            assert rc == 0, rc
+
+
 def capture(torch, fn):
     """Record fn(stream) into a HIP graph; returns a replay callable, or None if capture is not possible."""
     try:
@@ -459,6 +494,23 @@ def main():
         do_prefill()
         torch.cuda.synchronize()
 
+    ragged = None
+    if args.ragged_steps > 0 and B >= 2:
+        print("[bench] ragged batch through ec_decode_step_varlen", file=sys.stderr, flush=True)
+        do_decode()
+        torch.cuda.synchronize()
+        rd = RaggedDecode(wl, args.ragged_steps)
+        rd.run(wl._stream())
+        torch.cuda.synchronize()
+        fn = (capture(torch, rd.run) if use_graph else None) or (lambda: rd.run(wl._stream()))
+        fn()
+        r_ms = timed(torch, fn, 3) / (rd.steps * L)
+        ragged = {"cache_rows": [min(rd.lens), max(rd.lens)], "us_per_launch": r_ms * 1e3,
+                  "attn_GBps": rd.bytes_per_launch / (r_ms * 1e-3) / 1e9}
+        del rd
+        do_prefill()
+        torch.cuda.synchronize()
+
     n_dec = len(wl.decode_calls)
     dec_launch_us = decode_ms * 1e3 / n_dec
     dec_gbps = wl.decode_bytes / (decode_ms * 1e-3) / 1e9
@@ -503,6 +555,8 @@ def main():
         res["detail"]["turn2"] = turn2
     if freq_detail is not None:
         res["detail"]["frequency_policy"] = freq_detail
+    if ragged is not None:
+        res["detail"]["ragged_decode"] = ragged
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         res["cpu_baseline"] = cpu_baseline(cfg, wl, wl.G)

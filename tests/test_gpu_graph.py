@@ -78,3 +78,81 @@ def test_graph_replays_match_eager(dtype, D):
         assert torch.equal(bufs["kc"][:, :, :n_final], eager["kc"][:, :, :n_final]), replay
         assert torch.equal(bufs["vc"][:, :, :n_final], eager["vc"][:, :, :n_final]), replay
         assert torch.equal(bufs["pos"][:, :, :n_final], eager["pos"][:, :, :n_final]), replay
+
+
+def test_ragged_generation_loop_runs_from_one_graph_without_the_host():
+    """One captured graph = one generated token of a ragged batch: the retention test (Alg. 1's del_num, the
+    recent-distance victim of Sec. 4.1) runs as device integer arithmetic, ec_decode_step_varlen reads the
+    per-sequence numbers from device memory, and the lengths are updated on the device.  Replaying it must
+    equal the eager loop in which the host computes every index with ec_evict_index."""
+    dtype, B, H, D, steps, recent, pf = "bf16", 3, 4, 128, 30, 25, 1
+    p, qd = 1, 4
+    prompt = [160, 300, 480]
+    lens0 = [-(-t // qd) for t in prompt]                       # 40, 75, 120 rows after compression
+    cap = max(lens0) + steps + 1
+    rng = np.random.default_rng(5)
+    kc0 = torch.from_numpy(rng.standard_normal((B, H, cap, D)).astype(np.float32)).cuda().to(torch.bfloat16)
+    vc0 = torch.from_numpy(rng.standard_normal((B, H, cap, D)).astype(np.float32)).cuda().to(torch.bfloat16)
+    pos0 = torch.arange(cap, dtype=torch.int32, device="cuda").repeat(B, 1, 1).contiguous()
+    dq, dk, dv = (torch.from_numpy(rng.standard_normal((steps, B, H, D)).astype(np.float32)).cuda().to(torch.bfloat16)
+                  for _ in range(3))
+    i32 = lambda a: torch.tensor(a, dtype=torch.int32, device="cuda")
+
+    # eager loop, indices from the host
+    kc, vc, pos = kc0.clone(), vc0.clone(), pos0.clone()
+    lens, seen = list(lens0), list(prompt)
+    outs = torch.zeros((steps, B, H, D), dtype=torch.bfloat16, device="cuda")
+    n_evicted = 0
+    for s in range(steps):
+        seen = [n + 1 for n in seen]
+        vic = [ec.ec_evict_index(seen[b], lens[b] + 1, p, qd, recent=recent, protect_first=pf) for b in range(B)]
+        ec.ec_decode_step_varlen(dq[s], dk[s], dv[s], kc, vc, pos, i32(lens), i32(vic), i32([n - 1 for n in seen]),
+                                 0.088, outs[s])
+        lens = [n + (0 if v >= 0 else 1) for n, v in zip(lens, vic)]
+        n_evicted += sum(v >= 0 for v in vic)
+    torch.cuda.synchronize()
+    assert 0 < n_evicted < steps * B                            # both branches were taken
+
+    # the same loop as ONE graph replayed `steps` times; all state lives on the device
+    g_kc, g_vc, g_pos = kc0.clone(), vc0.clone(), pos0.clone()
+    g_len, g_seen = i32(lens0), i32(prompt)
+    g_vic, g_newpos = torch.zeros(B, dtype=torch.int32, device="cuda"), torch.zeros(B, dtype=torch.int32, device="cuda")
+    q_in, k_in, v_in = (torch.zeros((B, H, D), dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    g_out = torch.zeros((B, H, D), dtype=torch.bfloat16, device="cuda")
+
+    def one_token():
+        g_seen.add_(1)
+        keep = (g_seen * p + (qd - 1)) // qd                    # ceil(gamma * tokens seen)
+        vic = torch.clamp_min(g_len - recent, pf)               # (len + 1) - 1 - recent, raised to protect_first
+        go = ((g_len + 1) > keep) & (vic < g_len)
+        g_vic.copy_(torch.where(go, vic, torch.full_like(vic, -1)).to(torch.int32))
+        g_newpos.copy_((g_seen - 1).to(torch.int32))
+        ec.ec_decode_step_varlen(q_in, k_in, v_in, g_kc, g_vc, g_pos, g_len, g_vic, g_newpos, 0.088, g_out)
+        g_len.add_((~go).to(torch.int32))
+
+    # warm-up on throw-away state, then capture
+    saved = [t.clone() for t in (g_kc, g_vc, g_pos, g_len, g_seen)]
+    one_token()
+    torch.cuda.synchronize()
+    for t, s_ in zip((g_kc, g_vc, g_pos, g_len, g_seen), saved):
+        t.copy_(s_)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            one_token()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for t, s_ in zip((g_kc, g_vc, g_pos, g_len, g_seen), saved):   # capture does not execute, but be explicit
+        t.copy_(s_)
+    for s in range(steps):
+        q_in.copy_(dq[s]); k_in.copy_(dk[s]); v_in.copy_(dv[s])
+        g.replay()
+        assert torch.equal(g_out, outs[s]), s
+    torch.cuda.synchronize()
+    assert g_len.cpu().tolist() == lens
+    for b in range(B):
+        n = lens[b]
+        assert torch.equal(g_kc[b, :, :n], kc[b, :, :n]) and torch.equal(g_vc[b, :, :n], vc[b, :, :n])
+        assert torch.equal(g_pos[b, :, :n], pos[b, :, :n])
