@@ -296,6 +296,35 @@ class RaggedDecode:
             assert rc == 0, rc
 
 
+class FoldedDecode:
+    """Layers folded into the batch: ONE ec_decode_step launch over all layers' caches of a token step.  Legal only
+    because the synthetic decode inputs of a layer do not depend on the layer below; reported for small batches,
+    where a per-layer launch has too few (batch, head) pairs to fill the chip."""
+
+    def __init__(self, wl, launches):
+        import torch
+        from paper_2407_18121_amd import synthetic_torch as synt
+        cfg = wl.cfg
+        self.wl, self.lib = wl, wl.lib
+        B, H, D, L, G, cap = cfg.B, cfg.H, cfg.D, cfg.layers, wl.G, cfg.cap
+        dt = synt.torch_dtype(cfg)
+        N = min(wl.final_len, cap - 1)
+        self.N, self.launches = N, launches
+        g = torch.Generator(device="cuda").manual_seed(11)
+        self.kc = torch.randn((L * B, H, cap, D), generator=g, device="cuda").to(dt)
+        self.vc = torch.randn((L * B, H, cap, D), generator=g, device="cuda").to(dt)
+        self.q, self.kn, self.vn = (torch.randn((L * B, H, D), generator=g, device="cuda").to(dt) for _ in range(3))
+        self.out = torch.empty((L * B, H, D), dtype=dt, device="cuda")
+        self.call = (self.q.data_ptr(), self.kn.data_ptr(), self.vn.data_ptr(), self.kc.data_ptr(), self.vc.data_ptr(), None,
+                     L * B, H, G, D, cap, N, max(N - 25, 1), 0, cfg.scale, wl.dt_code, self.out.data_ptr(), None, 0)
+        self.bytes_per_launch = 2.0 * L * B * H * (N + 1) * D * cfg.esize
+
+    def run(self, s):
+        for _ in range(self.launches):
+            rc = self.lib.ec_decode_step(*self.call, s)
+            assert rc == 0, rc
+
+
 def capture(torch, fn):
     """Record fn(stream) into a HIP graph; returns a replay callable, or None if capture is not possible."""
     try:
@@ -511,6 +540,29 @@ def main():
         do_prefill()
         torch.cuda.synchronize()
 
+    folded = None
+    if B * cfg.H < 256 and L > 1:
+        print("[bench] layers-folded decode launch", file=sys.stderr, flush=True)
+        fo = FoldedDecode(wl, 16)
+        fo.run(wl._stream())
+        torch.cuda.synchronize()
+        fn = (capture(torch, fo.run) if use_graph else None) or (lambda: fo.run(wl._stream()))
+        fn()
+        fo_ms = timed(torch, fn, 3) / fo.launches
+        folded = {"note": "all layers of one token step in ONE launch (layers as batch); legal only for synthetic inputs",
+                  "cache_rows": fo.N, "us_per_launch": fo_ms * 1e3, "attn_GBps": fo.bytes_per_launch / (fo_ms * 1e-3) / 1e9,
+                  "frac_of_hbm_peak": fo.bytes_per_launch / (fo_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                  "tokens_per_s_if_folded": B / (fo_ms * 1e-3)}
+        del fo
+    # a plain device copy on the same box, for a measured ceiling beside the nominal one
+    cp_src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    cp_dst = torch.empty_like(cp_src)
+    cp_dst.copy_(cp_src)
+    copy_ms = timed(torch, lambda: cp_dst.copy_(cp_src), 5)
+    copy_gbps = 2.0 * cp_src.numel() / (copy_ms * 1e-3) / 1e9
+    del cp_src, cp_dst
+    step_ms = sorted(e[0].elapsed_time(e[2]) for e in ev)
+
     n_dec = len(wl.decode_calls)
     dec_launch_us = decode_ms * 1e3 / n_dec
     dec_gbps = wl.decode_bytes / (decode_ms * 1e-3) / 1e9
@@ -538,12 +590,15 @@ def main():
             "score_TFLOPs": score_tflops, "score_frac_of_peak": score_tflops / score_peak,
             "merge_GBps": merge_gbps, "merge_frac_of_hbm_peak": merge_gbps / HBM_PEAK_GBPS,
             "wall_ms_per_step": wall_ms, "event_ms_per_step": prefill_ms + decode_ms,
+            "event_ms_per_step_min": step_ms[0], "event_ms_per_step_median": step_ms[len(step_ms) // 2],
+            "device_copy_GBps": copy_gbps,
         },
         "roofline": {
             "kernel": "decode_step_kernel", "bound": "hbm", "achieved": dec_gbps, "peak": HBM_PEAK_GBPS,
             "unit": "GB/s", "frac": dec_gbps / HBM_PEAK_GBPS,
             "traffic": (DECODE_TRAFFIC_RATIO[cfg.name] * wl.decode_bytes / n_dec) if cfg.name in DECODE_TRAFFIC_RATIO else None,
             "bytes_per_launch": wl.decode_bytes / n_dec, "us_per_launch": dec_launch_us,
+            "frac_of_measured_copy": dec_gbps / copy_gbps,
         },
         "roofline_score": {
             "kernel": "prefill score (attention + column mass)", "bound": "mfma" if cfg.dtype == "bf16" else "alu",
@@ -557,6 +612,8 @@ def main():
         res["detail"]["frequency_policy"] = freq_detail
     if ragged is not None:
         res["detail"]["ragged_decode"] = ragged
+    if folded is not None:
+        res["detail"]["decode_layers_folded"] = folded
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         res["cpu_baseline"] = cpu_baseline(cfg, wl, wl.G)

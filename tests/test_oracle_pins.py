@@ -474,3 +474,46 @@ def test_evict_min_against_numpy(G):
     assert victim[1, 0] == 3
     with pytest.raises(ValueError):
         oracle.evict_min(freq, kc, vc, pos, 3, 2, 1)   # nothing left to choose from
+
+
+# ----------------------------------------------------------------- fixed-point elimination over a whole generation
+@pytest.mark.parametrize("T,p,q,steps", [(200, 1, 2, 90), (333, 1, 4, 120), (400, 1, 10, 70)])
+def test_fixed_point_survivors_in_closed_form(T, p, q, steps):
+    """With the recent distance R = 25 (Sec. 4.1) the victim is always the row that has exactly R rows behind
+    it, i.e. the row that just left the window of the R newest.  So a row survives iff the step at which it
+    leaves that window is one where the retention test keeps everything (Alg. 1's del_num = 0); rows deeper
+    than the window at the start are never touched.  The oracle's position bookkeeping must show exactly that.
+    (Caches longer than R rows; shorter ones raise the victim to protect_first, covered with the edge cases.)"""
+    R, H, D = 25, 1, 2
+    n0 = -(-p * T // q)
+    assert n0 > R
+    cap = n0 + steps + 1
+    rng = np.random.default_rng(T)
+    kc, vc = rng.standard_normal((1, H, cap, D)), rng.standard_normal((1, H, cap, D))
+    anchors = np.sort(rng.choice(T, n0, replace=False)).astype(np.int32)
+    pos = np.zeros((1, 1, cap), np.int32)
+    pos[0, 0, :n0] = anchors
+    N = n0
+    evicting = {}
+    for t in range(1, steps + 1):
+        idx = oracle.evict_index(T + t, N + 1, p, q, recent=R)
+        evicting[t] = idx >= 0
+        before = pos[0, 0, :N].copy()
+        oracle.decode_step(rng.standard_normal((1, H, D)), rng.standard_normal((1, H, D)), rng.standard_normal((1, H, D)),
+                           kc, vc, pos, N, idx, T + t - 1, 0.5)
+        if idx >= 0:
+            np.testing.assert_array_equal(pos[0, 0, :idx], before[:idx])            # rows before the victim stay
+            np.testing.assert_array_equal(pos[0, 0, idx:N - 1], before[idx + 1:])   # rows behind it move up by one
+            assert pos[0, 0, N - 1] == T + t - 1                                    # the new row closes the cache
+        else:
+            N += 1
+        assert N == -(-p * (T + t) // q)                                            # ceil(gamma * tokens seen)
+        assert (np.diff(pos[0, 0, :N]) > 0).all()
+    # items in arrival order: the anchors, then the generated tokens T, T+1, ...
+    items = list(anchors) + [T + t - 1 for t in range(1, steps + 1)]
+    survivors = []
+    for i, item in enumerate(items):
+        leaves_at = i - (n0 - R) + 1          # the step at which R rows stand behind it
+        if leaves_at < 1 or leaves_at > steps or not evicting[leaves_at]:
+            survivors.append(item)
+    np.testing.assert_array_equal(pos[0, 0, :N], np.array(survivors, np.int32))
