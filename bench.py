@@ -15,7 +15,7 @@ batches of two or more, `--ragged-steps` tokens of a mixed-length batch through 
 (`detail.ragged_decode`).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--score-mode layer|head]
-                    [--no-graph] [--no-cpu-baseline] [--turn2 N]
+                    [--no-graph] [--no-cpu-baseline] [--turn2 N] [--freq-steps N] [--ragged-steps N] [--no-extras]
 """
 from __future__ import annotations
 
@@ -55,9 +55,15 @@ def parse():
                     help="generated tokens timed under the frequency discard policy after the main step (0 = skip)")
     ap.add_argument("--ragged-steps", type=int, default=16,
                     help="generated tokens timed through ec_decode_step_varlen on a mixed-length batch (0 = skip; needs B >= 2)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the main step: no second turn, frequency policy, ragged or layers-folded runs "
+                         "(kernel traces then hold the main path's launches alone)")
     ap.add_argument("--distinct-layers", type=int, default=0,
                     help="distinct prompt tensors to generate (0 = one per layer; fewer are cycled)")
-    return ap.parse_args()
+    args = ap.parse_args()
+    if args.no_extras:
+        args.turn2 = args.freq_steps = args.ragged_steps = 0
+    return args
 
 
 class Workload:
@@ -541,7 +547,7 @@ def main():
         torch.cuda.synchronize()
 
     folded = None
-    if B * cfg.H < 256 and L > 1:
+    if B * cfg.H < 256 and L > 1 and not args.no_extras:
         print("[bench] layers-folded decode launch", file=sys.stderr, flush=True)
         fo = FoldedDecode(wl, 16)
         fo.run(wl._stream())

@@ -316,30 +316,41 @@ int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k
 }
 
 // ------------------------------------------------------------------ frequency discard policy
-// freq[b,g,j] += this step's attention mass of row j (head mean when G == 1, heads added in ascending
-// order); the row just appended (j = n - 1) starts at its own mass.
-__global__ __launch_bounds__(256) void freq_accumulate_kernel(const float* __restrict__ raw,
-                                                              const float* __restrict__ stats,
-                                                              float* __restrict__ freq, int H, int G, int n, int cap)
+// freq[b,g,j] += this step's attention mass of row j (head mean when G == 1); the row just appended
+// (j = n - 1) starts at its own mass.  A workgroup covers 64 rows; its 4 thread groups each add up a quarter
+// of the heads (ascending), and the quarters are added in ascending order: the result does not depend on
+// scheduling.
+constexpr int kFreqRows = 64;
+constexpr int kFreqParts = 4;
+__global__ __launch_bounds__(kFreqRows * kFreqParts) void freq_accumulate_kernel(const float* __restrict__ raw,
+                                                                                const float* __restrict__ stats,
+                                                                                float* __restrict__ freq, int H, int G,
+                                                                                int n, int cap)
 {
+    __shared__ float part[kFreqParts][kFreqRows];
     const int bg = blockIdx.y;
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= n) return;
+    const int r = threadIdx.x % kFreqRows, grp = threadIdx.x / kFreqRows;
+    const int j = blockIdx.x * kFreqRows + r;
     const int b = bg / G, g = bg % G;
-    float mass;
-    if (G == H) {
-        const size_t bh = (size_t)b * H + g;
-        mass = exp2f(raw[bh * cap + j] - stats[bh * 2]) / stats[bh * 2 + 1];
-    } else {
-        float acc = 0.f;
-        for (int h = 0; h < H; ++h) {
+    const int h_first = (G == H) ? g : 0, h_count = (G == H) ? 1 : H;
+    const int per = (h_count + kFreqParts - 1) / kFreqParts;
+    const int h0 = h_first + grp * per, h1 = min(h0 + per, h_first + h_count);
+    float acc = 0.f;
+    if (j < n)
+        for (int h = h0; h < h1; ++h) {
             const size_t bh = (size_t)b * H + h;
             acc += exp2f(raw[bh * cap + j] - stats[bh * 2]) / stats[bh * 2 + 1];
         }
-        mass = acc / (float)H;
+    part[grp][r] = acc;
+    __syncthreads();
+    if (grp == 0 && j < n) {
+        float mass = part[0][r];
+#pragma unroll
+        for (int p = 1; p < kFreqParts; ++p) mass += part[p][r];
+        mass /= (float)h_count;
+        float* f = freq + (size_t)bg * cap + j;
+        *f = (j == n - 1) ? mass : *f + mass;
     }
-    float* f = freq + (size_t)bg * cap + j;
-    *f = (j == n - 1) ? mass : *f + mass;
 }
 
 template <int DT, int D, int WAVES>
@@ -356,8 +367,8 @@ static int launch_decode_score(const void* q, const void* k_new, const void* v_n
     int rc = status_from_hip(hipGetLastError());
     if (rc != EC_OK) return rc;
     const int n = cache_len + 1;
-    hipLaunchKernelGGL(freq_accumulate_kernel, dim3((n + 255) / 256, B * G), dim3(256), 0, stream, raw, stats, freq,
-                       H, G, n, cap);
+    hipLaunchKernelGGL(freq_accumulate_kernel, dim3((n + kFreqRows - 1) / kFreqRows, B * G),
+                       dim3(kFreqRows * kFreqParts), 0, stream, raw, stats, freq, H, G, n, cap);
     return status_from_hip(hipGetLastError());
 }
 
