@@ -236,3 +236,14 @@ def evict_min(freq_f32, k_cache, v_cache, pos, length: int, protect_first: int =
     if rc:
         raise ValueError(f"oracle_evict_min rc={rc}")
     return victim
+
+
+def importance_mean(score, Tq: int, P: int = 0):
+    """Table 3d's "Mean" metric from the column sums: score [B,G,P+Tq] fp64 -> new array, sum / number of seeing queries."""
+    s = np.array(score, dtype=np.float64, order="C", copy=True)
+    B, G, L = s.shape
+    assert L == P + Tq
+    rc = _load().oracle_importance_mean(_d(s), B, G, Tq, P)
+    if rc:
+        raise ValueError(f"oracle_importance_mean rc={rc}")
+    return s

@@ -578,3 +578,23 @@ int oracle_evict_min(float *freq, double *k_cache, double *v_cache, int32_t *pos
         }
     return 0;
 }
+
+/* ------------------------------------------------------------------------- */
+/* "Mean" importance metric of the ablation (Table 3d) next to the default    */
+/* "Sum": the column mass divided by the number of queries that can see the   */
+/* key.  In a pass of Tq queries over P cached rows + the chunk (P = 0: the   */
+/* prompt pass) row n is seen by queries m >= max(0, n - P), i.e. by           */
+/* Tq - max(0, n - P) of them.  score [B,G,P+Tq], in place.                   */
+/* ------------------------------------------------------------------------- */
+int oracle_importance_mean(double *score, int B, int G, int Tq, int P)
+{
+    if (B < 1 || G < 1 || Tq < 1 || P < 0) return 1;
+    const int L = P + Tq;
+    for (size_t bg = 0; bg < (size_t)B * G; ++bg)
+        for (int n = 0; n < L; ++n) {
+            int first = n - P;
+            if (first < 0) first = 0;
+            score[bg * L + n] /= (double)(Tq - first);
+        }
+    return 0;
+}

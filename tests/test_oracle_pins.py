@@ -517,3 +517,19 @@ def test_fixed_point_survivors_in_closed_form(T, p, q, steps):
         if leaves_at < 1 or leaves_at > steps or not evicting[leaves_at]:
             survivors.append(item)
     np.testing.assert_array_equal(pos[0, 0, :N], np.array(survivors, np.int32))
+
+
+# ----------------------------------------------------------------- "Mean" importance metric (Table 3d)
+@pytest.mark.parametrize("Tq,P", [(13, 0), (9, 6), (1, 5)])
+def test_importance_mean_is_the_mean_over_the_seeing_queries(Tq, P):
+    B, H, D, L = 2, 2, 4, P + Tq
+    q, k, v = _rand((B, H, Tq, D), 71), _rand((B, H, L, D), 72), _rand((B, H, L, D), 73)
+    r = oracle.chunk_score(q, k, v, P, 0.5, H)
+    got = oracle.importance_mean(r["score"], Tq, P)
+    tq, tk = torch.from_numpy(q), torch.from_numpy(k)
+    mask = torch.arange(L)[None, :] <= (P + torch.arange(Tq))[:, None]
+    s = (0.5 * torch.einsum("bhmd,bhnd->bhmn", tq, tk)).masked_fill(~mask, float("-inf"))
+    A = torch.softmax(s, -1).numpy()
+    A[..., ~mask.numpy()] = np.nan                     # entries a query cannot see do not enter the mean
+    np.testing.assert_allclose(got, np.nanmean(A, axis=-2), atol=1e-13)
+    assert got is not r["score"] and not np.shares_memory(got, r["score"])
