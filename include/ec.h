@@ -130,6 +130,15 @@ int ec_chunk_score(const void* q, const void* k, const void* v, void* out, float
                    void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The "Mean" importance metric of the ablation on the importance metric (Table 3d), from the "Sum" the
+ * scoring calls emit: every score is divided, in place, by the number of queries that can see its row.
+ * After ec_prefill_score pass T_new = T, P = 0 (row n is seen by T - n queries); after ec_chunk_score pass
+ * its T_new and P (row n is seen by T_new - max(0, n - P) queries).
+ *   score  DEVICE [B,G,P+T_new] float, updated in place
+ */
+int ec_importance_mean(float* score, int B, int G, int T_new, int P, void* stream);
+
+/*
  * Anchor selection (Sec. 3.3: "top N_I tokens in I_n, indices in ascending
  * order"; Sec. 4.1: the first and the most recent token are protected).
  * For every (b,g): positions 0..protect_first-1 and T-protect_last..T-1 are

@@ -25,7 +25,7 @@ EC_MERGE_MEAN, EC_MERGE_EVICT = 0, 1
 SYMBOLS = ("ec_status_string", "ec_workspace_bytes", "ec_prefill_score", "ec_chunk_score", "ec_select_anchors",
            "ec_merge_compact", "ec_remerge_compact", "ec_evict_index", "ec_decode_step", "ec_decode_score_step",
            "ec_evict_min", "ec_prefill_score_varlen", "ec_select_anchors_varlen", "ec_merge_compact_varlen",
-           "ec_decode_step_varlen")
+           "ec_decode_step_varlen", "ec_importance_mean")
 
 _lib = None
 
@@ -77,6 +77,8 @@ def load():
     lib.ec_merge_compact_varlen.restype = c_int
     lib.ec_decode_step_varlen.argtypes = [c_vp] * 9 + [c_int] * 5 + [c_f, c_int, c_vp, c_vp, c_sz, c_vp]
     lib.ec_decode_step_varlen.restype = c_int
+    lib.ec_importance_mean.argtypes = [c_vp] + [c_int] * 4 + [c_vp]
+    lib.ec_importance_mean.restype = c_int
     _lib = lib
     return lib
 
@@ -301,4 +303,15 @@ def ec_decode_step_varlen(q, k_new, v_new, k_cache, v_cache, pos, cache_len_b, e
                                       cap, scale, dtype_code(k_cache), _ptr(out, "out"), None, 0, _stream())
     if check and rc != EC_OK:
         raise EcError("ec_decode_step_varlen", rc)
+    return rc
+
+
+def ec_importance_mean(score, T_new: int, P: int = 0, check=True) -> int:
+    """Table 3d's "Mean" metric, in place: score [B,G,P+T_new] f32 divided by the number of seeing queries."""
+    B, G, L = score.shape
+    if L != P + T_new or score.dtype != torch.float32:
+        raise ValueError("ec_importance_mean: score must be float32 [B,G,P+T_new]")
+    rc = load().ec_importance_mean(_ptr(score, "score"), B, G, T_new, P, _stream())
+    if check and rc != EC_OK:
+        raise EcError("ec_importance_mean", rc)
     return rc

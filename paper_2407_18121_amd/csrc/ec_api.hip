@@ -29,6 +29,7 @@ int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, 
                         float* head_imp, void* vt, int B, int H, ScoreGeom geo, const int32_t* seq_len, int D,
                         int dt, float scale, int forced_waves, hipStream_t stream);
 size_t score_mfma_vt_bytes(int B, int H, int T, int D);
+int importance_mean_launch(float* score, int B, int G, int Tq, int P, hipStream_t stream);
 int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, hipStream_t stream);
 }  // namespace ec
 
@@ -145,6 +146,13 @@ int ec_chunk_score(const void* q, const void* k, const void* v, void* out, float
     if (T_new < 1 || P < 0 || (long long)P + T_new > 0x7fffffffLL / 2) return EC_EINVAL;
     return score_pass(q, k, v, out, lse, score, B, H, G, ec::ScoreGeom{T_new, P, P + T_new, kv_rows, T_new, P + T_new},
                       nullptr, D, dt, scale, ws, ws_bytes, stream);
+}
+
+int ec_importance_mean(float* score, int B, int G, int T_new, int P, void* stream)
+{
+    if (!score) return EC_EINVAL;
+    if (B < 1 || G < 1 || T_new < 1 || P < 0 || (long long)P + T_new > 0x7fffffffLL / 2) return EC_EINVAL;
+    return ec::importance_mean_launch(score, B, G, T_new, P, reinterpret_cast<hipStream_t>(stream));
 }
 
 int ec_select_anchors(const float* score, int B, int G, int T, int n_anchor, int protect_first,

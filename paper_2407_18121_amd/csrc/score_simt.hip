@@ -265,6 +265,25 @@ int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, h
     return status_from_hip(hipGetLastError());
 }
 
+// "Mean" importance metric: column mass over the number of queries that see the row (in place).
+__global__ __launch_bounds__(256) void importance_mean_kernel(float* __restrict__ score, int Tq, int P, size_t rows)
+{
+    const int L = P + Tq;
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= L) return;
+    const float seen = (float)(Tq - max(n - P, 0));
+    for (size_t r = blockIdx.y; r < rows; r += gridDim.y) score[r * L + n] /= seen;
+}
+
+int importance_mean_launch(float* score, int B, int G, int Tq, int P, hipStream_t stream)
+{
+    const size_t rows = (size_t)B * G;
+    const int L = P + Tq;
+    hipLaunchKernelGGL(importance_mean_kernel, dim3((L + 255) / 256, (unsigned)(rows < 65535 ? rows : 65535)), dim3(256), 0,
+                       stream, score, Tq, P, rows);
+    return status_from_hip(hipGetLastError());
+}
+
 template <int DT, int D>
 static int launch_simt(const void* q, const void* k, const void* v, void* out, float* lse,
                        float* head_imp, int B, int H, ScoreGeom geo, const int32_t* seq_len, float scale,

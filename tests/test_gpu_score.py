@@ -57,3 +57,16 @@ def test_tiny_config_full_layer():
         assert_close(out, ref["out"], cfg.dtype, "out")
         assert_close(lse, ref["lse"], cfg.dtype, "lse")
         assert_close(score, ref["score"], cfg.dtype, "score")
+
+
+@pytest.mark.parametrize("B,G,Tq,P", [(2, 3, 300, 0), (1, 1, 37, 120), (3, 2, 1, 64), (1, 4, 5000, 700)])
+def test_importance_mean_metric(B, G, Tq, P):
+    """Table 3d's "Mean" metric: the sums divided by the number of queries that see each row."""
+    rng = np.random.default_rng(Tq + P)
+    L = P + Tq
+    sums = (rng.random((B, G, L)) * (1.0 + 300.0 / (1 + np.arange(L)))).astype(np.float32)
+    ref = oracle.importance_mean(sums.astype(np.float64), Tq, P)
+    d = torch.from_numpy(sums).cuda()
+    ec.ec_importance_mean(d, Tq, P)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(d.cpu().numpy().astype(np.float64), ref, rtol=3e-7, atol=0)   # one fp32 division
