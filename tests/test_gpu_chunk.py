@@ -267,3 +267,23 @@ def test_layer_state_second_turn_calls_the_same_entry_points():
     assert torch.equal(npos[:, :, :n2], st.pos[:, :, :n2])
     p = st.pos[0, 0, :n2].cpu().numpy()
     assert (np.diff(p) > 0).all() and p[0] == 0 and p[-1] == T1 + 40 + T2 - 1   # original positions stay ordered
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
+def test_chunk_score_tile_boundary_sweep(dtype, D):
+    """Every combination of prefix and chunk lengths at, just below and just above the kernels' tile sizes
+    (32, 64, 128, 256): the shifted diagonal crosses the tiles at every possible offset."""
+    edges = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257]
+    H, B = 2, 1
+    worst = 0.0
+    for P in [0] + edges:
+        for Tq in edges:
+            q, k, v, scale = _chunk_inputs(B, H, Tq, P, D, dtype, 5000 + P * 1000 + Tq)
+            ref = oracle.chunk_score(q, k, v, P, scale, 1)
+            out, lse, score = run_gpu_chunk(q, k, v, P, 1, dtype, scale, 1)
+            for name, got, want in (("out", out, ref["out"]), ("lse", lse, ref["lse"]), ("score", score, ref["score"])):
+                assert np.isfinite(got).all(), (P, Tq, name)
+                err = np.abs(got - want).max()
+                worst = max(worst, err)
+                assert err <= (2e-2 if dtype == "bf16" else 1e-4), (P, Tq, name, err)
+    print(f"worst abs error over the sweep: {worst:.2e}")
