@@ -123,3 +123,13 @@ def test_generation_run_tiny_config():
     np.testing.assert_array_equal(to_host(dvc)[:, :, :N], ovc[:, :, :N])
     np.testing.assert_array_equal(dpos.cpu().numpy()[:, :, :N], opos[:, :, :N])
     assert N == 144 and (np.diff(opos[0, 0, :N]) > 0).all()
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
+def test_decode_length_and_victim_sweep(dtype, D):
+    """Cache lengths at, just below and just above the kernel's tile sizes, each with no victim, the first row,
+    a middle row, the recent-distance row and the new row itself as the victim."""
+    for n in [0, 1, 2, 3, 15, 16, 17, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 255, 256, 257, 511, 512, 513]:
+        victims = {-1, 0, n // 2, max(n - 25, 0), n}
+        for vic in sorted(victims):
+            _case(dtype, D, B=1, H=2, G=1, cap=n + 2, cache_len=n, evict_idx=vic, seed=7000 + n * 10 + vic)
