@@ -234,3 +234,54 @@ def test_second_turn_full_shape(name):
     _assert_valid_selection(sc, a)
     np.testing.assert_array_equal(counts.cpu().numpy().sum(-1), weights.cpu().numpy().sum(-1))
     assert torch.isfinite(nk.float()).all() and torch.isfinite(nv.float()).all()
+
+
+def test_long_prompt_beyond_the_workloads():
+    """A prompt 2.4x the longest workload, of a length no tile size divides: the select kernel's keys no
+    longer fit in LDS, the key-tile loops run 300+ iterations, and a cache of 30000 rows is decoded."""
+    B, H, D, T, dtype = 1, 2, 128, 20011, "bf16"
+    cfg = syn.custom("long", H=H, D=D, B=B, T=T, dtype=dtype, gamma=(1, 10), cid=4242)
+    q, k, v = synt.prompt_qkv_device(cfg, layer=0)
+    out = torch.empty_like(q)
+    lse = torch.empty((B, H, T), dtype=torch.float32, device="cuda")
+    score = torch.empty((B, 1, T), dtype=torch.float32, device="cuda")
+    ws = ec.new_workspace(ec.EC_FN_PREFILL_SCORE, B, H, T, D, ec.EC_BF16)
+    ec.ec_prefill_score(q, k, v, out, lse, score, cfg.scale, ws)
+    torch.cuda.synchronize()
+    ref = oracle.prefill_score(_host(q), _host(k), _host(v), cfg.scale, 1)
+    assert_close(to_host(out), ref["out"], dtype, "out")
+    assert_close(to_host(lse), ref["lse"], dtype, "lse")
+    assert_close(_host(score), ref["score"], dtype, "score")
+    nA = -(-T // 10)
+    sc32 = ref["score"].astype(np.float32)
+    a_ref = oracle.select_anchors(sc32, nA, 1, 1)
+    a_gpu = torch.empty((B, 1, nA), dtype=torch.int32, device="cuda")
+    ec.ec_select_anchors(torch.from_numpy(sc32).cuda(), nA, 1, 1, a_gpu)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(a_gpu.cpu().numpy(), a_ref)
+    assign, counts = oracle.assign_nearest(a_ref, T)
+    kc = torch.zeros((B, H, nA, D), dtype=q.dtype, device="cuda")
+    vc = torch.zeros_like(kc)
+    d_counts = torch.empty((B, 1, nA), dtype=torch.int32, device="cuda")
+    ec.ec_merge_compact(k, v, a_gpu, kc, vc, d_counts)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(d_counts.cpu().numpy(), counts)
+    assert_close(to_host(kc), oracle.merge_compact(_host(k), assign, nA), dtype, "k_cache", stored=True)
+    assert_close(to_host(vc), oracle.merge_compact(_host(v), assign, nA), dtype, "v_cache", stored=True)
+
+    # decode over a 30000-row cache with a victim deep inside it
+    N, cap = 30000, 30002
+    g = torch.Generator(device="cuda").manual_seed(99)
+    kc = (torch.randn((B, H, cap, D), generator=g, device="cuda") * 1.5).to(torch.bfloat16)
+    vc = torch.randn((B, H, cap, D), generator=g, device="cuda").to(torch.bfloat16)
+    pos = torch.arange(cap, dtype=torch.int32, device="cuda").repeat(B, 1, 1).contiguous()
+    dq, dk, dv = (torch.randn((B, H, D), generator=g, device="cuda").to(torch.bfloat16) for _ in range(3))
+    okc, ovc, opos = to_host(kc), to_host(vc), pos.cpu().numpy().copy()
+    dout = torch.empty((B, H, D), dtype=torch.bfloat16, device="cuda")
+    ec.ec_decode_step(dq, dk, dv, kc, vc, pos, N, 12345, 777777, cfg.scale, dout, None)
+    torch.cuda.synchronize()
+    o_ref, _ = oracle.decode_step(_host(dq), _host(dk), _host(dv), okc, ovc, opos, N, 12345, 777777, cfg.scale)
+    assert_close(to_host(dout), o_ref, dtype, "decode out")
+    np.testing.assert_array_equal(to_host(kc)[:, :, :N], okc[:, :, :N])
+    np.testing.assert_array_equal(to_host(vc)[:, :, :N], ovc[:, :, :N])
+    np.testing.assert_array_equal(pos.cpu().numpy()[:, :, :N], opos[:, :, :N])
