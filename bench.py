@@ -488,78 +488,71 @@ def main():
     do_prefill()  # restore the compressed caches for whoever looks at them next
     torch.cuda.synchronize()
 
-    turn2 = None
-    t2_len = cfg.T // 2 if args.turn2 < 0 else args.turn2
-    if t2_len > 0:
-        print(f"[bench] second turn: chunk of {t2_len} tokens over the generated cache", file=sys.stderr, flush=True)
+    # ---- rows beyond the core path, each outside `value`; a failure in one is reported, not fatal ----
+    def graph_or_eager(run):
+        fn = (capture(torch, run) if use_graph else None) or (lambda: run(wl._stream()))
+        fn()
+        return fn
+
+    def extra_turn2(t2_len):
         do_decode()   # leaves every layer's cache as the generation ends
         torch.cuda.synchronize()
         t2 = Turn2(wl, t2_len)
         t2.run_all(wl._stream())   # eager validation pass
         torch.cuda.synchronize()
-        def t2_ms(run):
-            fn = (capture(torch, run) if use_graph else None) or (lambda: run(wl._stream()))
-            fn()
-            return timed(torch, fn, 3) / L
+        t2_ms = lambda run: timed(torch, graph_or_eager(run), 3) / L
         a_ms, s_ms, sel_ms, m_ms = t2_ms(t2.run_all), t2_ms(t2.run_score), t2_ms(t2.run_select), t2_ms(t2.run_merge)
-        t2_tflops = t2.score_flops_per_layer / (s_ms * 1e-3) / 1e12
-        turn2 = {"chunk_tokens": t2_len, "cache_rows_before": t2.P, "cache_rows_after": t2.n2,
-                 "us_per_layer": a_ms * 1e3, "score_us_per_layer": s_ms * 1e3, "select_us_per_layer": sel_ms * 1e3,
-                 "merge_us_per_layer": m_ms * 1e3, "score_TFLOPs": t2_tflops,
-                 "merge_GBps": t2.merge_bytes_per_layer / (m_ms * 1e-3) / 1e9}
-        del t2
-        do_prefill()
-        torch.cuda.synchronize()
+        return {"chunk_tokens": t2_len, "cache_rows_before": t2.P, "cache_rows_after": t2.n2,
+                "us_per_layer": a_ms * 1e3, "score_us_per_layer": s_ms * 1e3, "select_us_per_layer": sel_ms * 1e3,
+                "merge_us_per_layer": m_ms * 1e3, "score_TFLOPs": t2.score_flops_per_layer / (s_ms * 1e-3) / 1e12,
+                "merge_GBps": t2.merge_bytes_per_layer / (m_ms * 1e-3) / 1e9}
 
-    freq_detail = None
-    if args.freq_steps > 0:
-        print("[bench] frequency discard policy at constant cache length", file=sys.stderr, flush=True)
+    def extra_frequency():
         do_decode()
         torch.cuda.synchronize()
         fd = FrequencyDecode(wl, args.freq_steps)
         fd.run(wl._stream())
         torch.cuda.synchronize()
-        fn = (capture(torch, fd.run) if use_graph else None) or (lambda: fd.run(wl._stream()))
-        fn()
-        f_ms = timed(torch, fn, 3) / (fd.steps * L)
-        freq_detail = {"cache_rows": fd.N, "steps": fd.steps, "us_per_layer_step": f_ms * 1e3,
-                       "attn_GBps": fd.bytes_per_layer_step / (f_ms * 1e-3) / 1e9,
-                       "launches_per_layer_step": 4}
-        del fd
-        do_prefill()
-        torch.cuda.synchronize()
+        f_ms = timed(torch, graph_or_eager(fd.run), 3) / (fd.steps * L)
+        return {"cache_rows": fd.N, "steps": fd.steps, "us_per_layer_step": f_ms * 1e3,
+                "attn_GBps": fd.bytes_per_layer_step / (f_ms * 1e-3) / 1e9, "launches_per_layer_step": 4}
 
-    ragged = None
-    if args.ragged_steps > 0 and B >= 2:
-        print("[bench] ragged batch through ec_decode_step_varlen", file=sys.stderr, flush=True)
+    def extra_ragged():
         do_decode()
         torch.cuda.synchronize()
         rd = RaggedDecode(wl, args.ragged_steps)
         rd.run(wl._stream())
         torch.cuda.synchronize()
-        fn = (capture(torch, rd.run) if use_graph else None) or (lambda: rd.run(wl._stream()))
-        fn()
-        r_ms = timed(torch, fn, 3) / (rd.steps * L)
-        ragged = {"cache_rows": [min(rd.lens), max(rd.lens)], "us_per_launch": r_ms * 1e3,
-                  "attn_GBps": rd.bytes_per_launch / (r_ms * 1e-3) / 1e9}
-        del rd
-        do_prefill()
-        torch.cuda.synchronize()
+        r_ms = timed(torch, graph_or_eager(rd.run), 3) / (rd.steps * L)
+        return {"cache_rows": [min(rd.lens), max(rd.lens)], "us_per_launch": r_ms * 1e3,
+                "attn_GBps": rd.bytes_per_launch / (r_ms * 1e-3) / 1e9}
 
-    folded = None
-    if B * cfg.H < 256 and L > 1 and not args.no_extras:
-        print("[bench] layers-folded decode launch", file=sys.stderr, flush=True)
+    def extra_folded():
         fo = FoldedDecode(wl, 16)
         fo.run(wl._stream())
         torch.cuda.synchronize()
-        fn = (capture(torch, fo.run) if use_graph else None) or (lambda: fo.run(wl._stream()))
-        fn()
-        fo_ms = timed(torch, fn, 3) / fo.launches
-        folded = {"note": "all layers of one token step in ONE launch (layers as batch); legal only for synthetic inputs",
-                  "cache_rows": fo.N, "us_per_launch": fo_ms * 1e3, "attn_GBps": fo.bytes_per_launch / (fo_ms * 1e-3) / 1e9,
-                  "frac_of_hbm_peak": fo.bytes_per_launch / (fo_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                  "tokens_per_s_if_folded": B / (fo_ms * 1e-3)}
-        del fo
+        fo_ms = timed(torch, graph_or_eager(fo.run), 3) / fo.launches
+        gbps = fo.bytes_per_launch / (fo_ms * 1e-3) / 1e9
+        return {"note": "all layers of one token step in ONE launch (layers as batch); legal only for synthetic inputs",
+                "cache_rows": fo.N, "us_per_launch": fo_ms * 1e3, "attn_GBps": gbps,
+                "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS, "tokens_per_s_if_folded": B / (fo_ms * 1e-3)}
+
+    def guarded(what, fn, *a):
+        print(f"[bench] {what}", file=sys.stderr, flush=True)
+        try:
+            r = fn(*a)
+        except Exception as e:   # the main line must still be printed
+            r = {"error": f"{type(e).__name__}: {e}"}
+        torch.cuda.synchronize()
+        do_prefill()             # back to the compressed caches of the main step
+        torch.cuda.synchronize()
+        return r
+
+    t2_len = cfg.T // 2 if args.turn2 < 0 else args.turn2
+    turn2 = guarded(f"second turn: chunk of {t2_len} tokens over the generated cache", extra_turn2, t2_len) if t2_len > 0 else None
+    freq_detail = guarded("frequency discard policy at constant cache length", extra_frequency) if args.freq_steps > 0 else None
+    ragged = guarded("ragged batch through ec_decode_step_varlen", extra_ragged) if args.ragged_steps > 0 and B >= 2 else None
+    folded = guarded("layers-folded decode launch", extra_folded) if B * cfg.H < 256 and L > 1 and not args.no_extras else None
     # a plain device copy on the same box, for a measured ceiling beside the nominal one
     cp_src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
     cp_dst = torch.empty_like(cp_src)
