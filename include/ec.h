@@ -160,8 +160,10 @@ int ec_select_anchors(const float* score, int B, int G, int T, int n_anchor, int
  * bucket j holds positions floor((t_{j-1}+t_j)/2)+1 .. floor((t_j+t_{j+1})/2), the
  * first bucket starting at 0 and the last ending at T-1 (every position goes to
  * its nearest anchor, ties to the earlier one).  For every head, cache row j is
- * the mean of the K (resp. V) rows of bucket j, accumulated in fp32 in ascending
- * position and rounded once (to nearest even) to dt.
+ * the mean of the K (resp. V) rows of bucket j, accumulated in fp32 and rounded
+ * once (to nearest even) to dt: in ascending position for buckets of up to 128
+ * rows, as interleaved partial sums added in a fixed order for longer ones
+ * (results are deterministic either way).
  *   k,v              DEVICE [B,H,T,D] dt, read only
  *   anchor_idx       DEVICE [B,G,n_anchor] int32 ascending, read only
  *   k_cache,v_cache  DEVICE [B,H,cap,D] dt; rows 0..n_anchor-1 written, rest untouched

@@ -7,13 +7,16 @@
 // it derives the bucket's bounds from the three neighbouring anchors, streams the
 // slab with 16-byte loads in ascending position, accumulates in fp32, divides by
 // the count once and stores the row.  Neighbouring groups own neighbouring
-// buckets, so a wave reads one contiguous stretch of the prompt.
+// buckets, so a wave reads one contiguous stretch of the prompt.  Importance scores
+// put most anchors next to each other and leave a few buckets of hundreds of rows:
+// those are summed by all lane groups of the workgroup together.
 #include "ec_common.h"
 
 namespace ec {
 
 constexpr int kMergeThreads = 256;
 constexpr int kMergeUnroll = 4;  // rows of K and of V in flight per bucket (8 loads per lane)
+constexpr int kMergeLong = 128;  // buckets with more rows are summed by the whole workgroup
 
 // Inclusive bounds of bucket j for ascending anchors a[0..n).  Clamped so that a
 // malformed anchor list can never index outside [0,T).
@@ -42,100 +45,160 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
     constexpr int LPR = D * Elem<DT>::kBytes / 16;
     constexpr int EPL = Elem<DT>::kPerChunk;
     constexpr int GROUPS = kMergeThreads / LPR;
+    __shared__ int sh_nlong;
+    __shared__ int sh_long[GROUPS];
+    __shared__ int sh_wsum[GROUPS];
+    __shared__ float sh_part[GROUPS][LPR * EPL * 2];
+
     const int bh = blockIdx.y;
     const int b = bh / H, h = bh % H;
-    const int sub = threadIdx.x % LPR;
+    const int tid = threadIdx.x;
+    const int sub = tid % LPR, grp = tid / LPR;
     // Long and short buckets sit at the same chunk numbers in every head, and workgroups go to the 8
     // XCDs round-robin by linear id: rotating the chunk number by the head index keeps the heavy chunks
     // from piling onto the same XCDs.
     const int chunk = (blockIdx.x + blockIdx.y) % gridDim.x;
-    const int j = chunk * GROUPS + threadIdx.x / LPR;
+    const int j = chunk * GROUPS + grp;
     // ragged batches: batch element b has T positions and n_anchor anchors; array rows stay T_max / n_max apart
     const int T = ragged_rows(seq_len, b, T_max);
     const int n_anchor = n_anchor_b ? min(max(n_anchor_b[b], 0), min(T, n_max)) : n_max;
-    if (j >= n_anchor) return;
+    if (chunk * GROUPS >= n_anchor) return;  // whole workgroup
+    const bool valid = j < n_anchor;
 
     const size_t bg = (size_t)b * G + (G == 1 ? 0 : h);
     const int32_t* a = anchor_idx + bg * n_max;
     const int32_t* wrow = WEIGHTED ? weights + bg * T_max : nullptr;
-    int lo, hi;
-    bucket_bounds(a, j, n_anchor, T, lo, hi);
-    const int blo = lo, bhi = hi;  // the bucket, for the bookkeeping
-    if (evict_only) lo = hi = min(max(a[j], 0), T - 1);  // eviction-only ablation: the anchor's own row
-
-    // K and V of the bucket are streamed side by side: two independent load streams per lane
+    const bool owner = (G == H || h == 0);  // writes the bookkeeping of its score group
+    // K and V of a bucket are streamed side by side: two independent load streams per lane
     const uint4* src_k = k + (size_t)bh * src_rows * LPR + sub;
     const uint4* src_v = v + (size_t)bh * src_rows * LPR + sub;
 
     float acc_k[EPL], acc_v[EPL];
+    int wsum;
+    // rows first, first + step, ... <= hi of one bucket; `whole` = this group sums the bucket alone
+    auto stream = [&](int first, int hi, int step, bool whole) {
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc_k[e] = acc_v[e] = 0.f;
-
-    // a bucket of one row is copied (weight 1 whatever it carries), so it stays bit-exact
-    const bool use_w = WEIGHTED && hi > lo;
-    int wsum = 0;
-    for (int t = lo; t <= hi; t += kMergeUnroll) {
-        uint4 ck[kMergeUnroll], cv[kMergeUnroll];
-        int wt[kMergeUnroll];
+        for (int e = 0; e < EPL; ++e) acc_k[e] = acc_v[e] = 0.f;
+        wsum = 0;
+        // a bucket of one row is copied (weight 1 whatever it carries), so it stays bit-exact
+        const bool use_w = WEIGHTED && !(whole && first == hi);
+        for (int t = first; t <= hi; t += kMergeUnroll * step) {
+            uint4 ck[kMergeUnroll], cv[kMergeUnroll];
+            int wt[kMergeUnroll];
 #pragma unroll
-        for (int u = 0; u < kMergeUnroll; ++u) {
-            ck[u] = make_uint4(0, 0, 0, 0);
-            cv[u] = make_uint4(0, 0, 0, 0);
-            wt[u] = 1;
-            if (t + u <= hi) {
-                if (WEIGHTED) wt[u] = max(wrow[t + u], 1);
-                ck[u] = load_stream(src_k + (size_t)(t + u) * LPR);
-                cv[u] = load_stream(src_v + (size_t)(t + u) * LPR);
+            for (int u = 0; u < kMergeUnroll; ++u) {
+                ck[u] = make_uint4(0, 0, 0, 0);
+                cv[u] = make_uint4(0, 0, 0, 0);
+                wt[u] = 1;
+                const int r = t + u * step;
+                if (r <= hi) {
+                    if (WEIGHTED) wt[u] = max(wrow[r], 1);
+                    ck[u] = load_stream(src_k + (size_t)r * LPR);
+                    cv[u] = load_stream(src_v + (size_t)r * LPR);
+                }
             }
-        }
 #pragma unroll
-        for (int u = 0; u < kMergeUnroll; ++u) {
-            if (t + u <= hi) {
-                float xk[EPL], xv[EPL];
-                unpack<DT>(ck[u], xk);
-                unpack<DT>(cv[u], xv);
-                const bool first = (u == 0 && t == lo);  // the sum starts from the first row, so a bucket
-                if (WEIGHTED) {                          // of one is a bit-exact copy (-0 stays -0)
-                    wsum += wt[u];
-                    const float w = use_w ? (float)wt[u] : 1.f;
+            for (int u = 0; u < kMergeUnroll; ++u) {
+                if (t + u * step <= hi) {
+                    float xk[EPL], xv[EPL];
+                    unpack<DT>(ck[u], xk);
+                    unpack<DT>(cv[u], xv);
+                    const bool start = (u == 0 && t == first);  // the sum starts from the first row, so a bucket
+                    if (WEIGHTED) {                             // of one is a bit-exact copy (-0 stays -0)
+                        wsum += wt[u];
+                        const float w = use_w ? (float)wt[u] : 1.f;
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) {
-                        acc_k[e] = first ? w * xk[e] : fmaf(w, xk[e], acc_k[e]);
-                        acc_v[e] = first ? w * xv[e] : fmaf(w, xv[e], acc_v[e]);
-                    }
-                } else {
+                        for (int e = 0; e < EPL; ++e) {
+                            acc_k[e] = start ? w * xk[e] : fmaf(w, xk[e], acc_k[e]);
+                            acc_v[e] = start ? w * xv[e] : fmaf(w, xv[e], acc_v[e]);
+                        }
+                    } else {
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) {
-                        acc_k[e] = first ? xk[e] : acc_k[e] + xk[e];
-                        acc_v[e] = first ? xv[e] : acc_v[e] + xv[e];
+                        for (int e = 0; e < EPL; ++e) {
+                            acc_k[e] = start ? xk[e] : acc_k[e] + xk[e];
+                            acc_v[e] = start ? xv[e] : acc_v[e] + xv[e];
+                        }
                     }
                 }
             }
         }
-    }
-    const int count = WEIGHTED ? wsum : hi - lo + 1;
-    if (hi > lo) {
-        const float cf = (float)count;
+    };
+    // divide by the count, round once, store cache row jj and its bookkeeping
+    auto finish = [&](int jj, int n_rows, int w_total) {
+        const int count = WEIGHTED ? w_total : n_rows;
+        if (n_rows > 1) {
+            const float cf = (float)count;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-            acc_k[e] = acc_k[e] / cf;
-            acc_v[e] = acc_v[e] / cf;
-        }
-    }
-    k_cache[((size_t)bh * cap + j) * LPR + sub] = pack<DT>(acc_k);
-    v_cache[((size_t)bh * cap + j) * LPR + sub] = pack<DT>(acc_v);
-
-    // bookkeeping, once per score group: bucket size, position of the cache row, bucket of every position
-    if (G == H || h == 0) {
-        if (sub == 0) {
-            if (counts) counts[bg * n_max + j] = count;
-            if (pos) {
-                const int t = min(max(a[j], 0), T - 1);
-                pos[bg * cap + j] = src_pos ? src_pos[bg * T_max + t] : a[j];
+            for (int e = 0; e < EPL; ++e) {
+                acc_k[e] = acc_k[e] / cf;
+                acc_v[e] = acc_v[e] / cf;
             }
         }
-        if (assign)
+        k_cache[((size_t)bh * cap + jj) * LPR + sub] = pack<DT>(acc_k);
+        v_cache[((size_t)bh * cap + jj) * LPR + sub] = pack<DT>(acc_v);
+        if (owner && sub == 0) {
+            if (counts) counts[bg * n_max + jj] = count;
+            if (pos) {
+                const int t = min(max(a[jj], 0), T - 1);
+                pos[bg * cap + jj] = src_pos ? src_pos[bg * T_max + t] : a[jj];
+            }
+        }
+    };
+
+    int lo = 0, hi = -1, blo = 0, bhi = -1;
+    if (valid) {
+        bucket_bounds(a, j, n_anchor, T, lo, hi);
+        blo = lo;
+        bhi = hi;  // the bucket, for the bookkeeping
+        if (evict_only) lo = hi = min(max(a[j], 0), T - 1);  // eviction-only ablation: the anchor's own row
+    }
+    // Buckets of more than kMergeLong rows are left to the whole workgroup (below): one lane group would
+    // stream them as a long chain of dependent loads while its neighbours sit idle.
+    const bool is_long = valid && (hi - lo + 1) > kMergeLong;
+    if (tid == 0) sh_nlong = 0;
+    __syncthreads();
+    if (is_long && sub == 0) sh_long[atomicAdd(&sh_nlong, 1)] = grp;
+    __syncthreads();
+
+    if (valid && !is_long) {
+        stream(lo, hi, 1, true);
+        finish(j, hi - lo + 1, wsum);
+        if (owner && assign)
             for (int t = blo + sub; t <= bhi; t += LPR) assign[bg * T_max + t] = (!evict_only || t == lo) ? j : -1;
+    }
+
+    // Long buckets, one after the other: group g sums rows lo+g, lo+g+GROUPS, ...; the partial sums are
+    // added in ascending group order, so the result does not depend on which bucket is taken first.
+    const int n_long = sh_nlong;
+    for (int i = 0; i < n_long; ++i) {
+        const int jj = chunk * GROUPS + sh_long[i];
+        int llo, lhi;
+        bucket_bounds(a, jj, n_anchor, T, llo, lhi);
+        stream(llo + grp, lhi, GROUPS, false);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            sh_part[grp][(sub * EPL + e) * 2] = acc_k[e];
+            sh_part[grp][(sub * EPL + e) * 2 + 1] = acc_v[e];
+        }
+        if (sub == 0) sh_wsum[grp] = wsum;
+        __syncthreads();
+        if (grp == 0) {
+            int w_total = 0;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc_k[e] = acc_v[e] = 0.f;
+            for (int g = 0; g < GROUPS; ++g) {
+                w_total += sh_wsum[g];
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) {
+                    acc_k[e] += sh_part[g][(sub * EPL + e) * 2];
+                    acc_v[e] += sh_part[g][(sub * EPL + e) * 2 + 1];
+                }
+            }
+            finish(jj, lhi - llo + 1, w_total);
+        }
+        if (owner && assign)
+            for (int t = llo + tid; t <= lhi; t += kMergeThreads) assign[bg * T_max + t] = jj;
+        __syncthreads();  // the partial sums are free again
     }
 }
 

@@ -143,3 +143,45 @@ def test_evict_only_mode_copies_anchor_rows(dtype, D, Gmode):
         for g in range(G):
             want_assign[b, g, a[b, g]] = np.arange(n)
     np.testing.assert_array_equal(d_assign.cpu().numpy(), want_assign)
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64), ("f32", 128)])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_merge_long_buckets_next_to_single_rows(dtype, D, weighted):
+    """The shape importance scores produce: anchors packed at the start, then a few buckets of hundreds of rows
+    (summed by the whole workgroup) between single-row ones, several of them in one workgroup's chunk."""
+    B, H, T = 2, 3, 3000
+    rng = np.random.default_rng(D + weighted)
+    k = quantize(rng.standard_normal((B, H, T, D)) * 2, dtype)
+    v = quantize(rng.standard_normal((B, H, T, D)), dtype)
+    a0 = list(range(10)) + [400, 401, 900, 1500, 1501, 1502, 2200, 2998, 2999]
+    a1 = [0, 129, 130, 700, 701, 702, 703, 1400, 2100, 2101, 2800, 2801, 2802, 2803, 2804, 2805, 2806, 2900, 2999]
+    a = np.array([a0, a1], np.int32).reshape(B, 1, -1)
+    n = a.shape[-1]
+    assign, counts = oracle.assign_nearest(a, T)
+    assert counts.max() > 500 and (counts == 1).any()
+    w = rng.integers(1, 9, (B, 1, T)).astype(np.int32)
+    if weighted:
+        ok, wsum = oracle.merge_weighted(k, assign, w, n)
+        ov, _ = oracle.merge_weighted(v, assign, w, n)
+    else:
+        ok, ov, wsum = oracle.merge_compact(k, assign, n), oracle.merge_compact(v, assign, n), counts
+    dk_c = torch.zeros((B, H, n, D), dtype=torch_dtype(dtype), device="cuda")
+    dv_c = torch.zeros_like(dk_c)
+    d_counts = torch.full((B, 1, n), -1, dtype=torch.int32, device="cuda")
+    d_assign = torch.full((B, 1, T), -1, dtype=torch.int32, device="cuda")
+    d_pos = torch.full((B, 1, n), -1, dtype=torch.int32, device="cuda")
+    ec.ec_remerge_compact(to_dev(k, dtype), to_dev(v, dtype), T, torch.from_numpy(a).cuda(), dk_c, dv_c,
+                          weights=torch.from_numpy(w).cuda() if weighted else None, counts=d_counts, assign=d_assign, pos=d_pos)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(d_counts.cpu().numpy(), wsum)
+    np.testing.assert_array_equal(d_assign.cpu().numpy(), assign)
+    np.testing.assert_array_equal(d_pos.cpu().numpy(), a)
+    assert_close(to_host(dk_c), ok, dtype, "k_cache", stored=True)
+    assert_close(to_host(dv_c), ov, dtype, "v_cache", stored=True)
+    # twice the same call gives the same bits (the long buckets' partial sums are combined in a fixed order)
+    dk2, dv2 = torch.zeros_like(dk_c), torch.zeros_like(dv_c)
+    ec.ec_remerge_compact(to_dev(k, dtype), to_dev(v, dtype), T, torch.from_numpy(a).cuda(), dk2, dv2,
+                          weights=torch.from_numpy(w).cuda() if weighted else None)
+    torch.cuda.synchronize()
+    assert torch.equal(dk2, dk_c) and torch.equal(dv2, dv_c)
