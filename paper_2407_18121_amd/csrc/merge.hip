@@ -15,7 +15,7 @@
 namespace ec {
 
 constexpr int kMergeThreads = 256;
-constexpr int kMergeUnroll = 4;  // rows of K and of V in flight per bucket (8 loads per lane)
+constexpr int kMergeUnroll = 8;  // rows of K and of V in flight per bucket (16 loads per lane)
 constexpr int kMergeLong = 128;  // buckets with more rows are summed by the whole workgroup
 
 // Inclusive bounds of bucket j for ascending anchors a[0..n).  Clamped so that a
