@@ -280,6 +280,24 @@ int ec_decode_step_varlen(const void* q, const void* k_new, const void* v_new, v
                           void* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * ec_evict_index for every sequence of a ragged batch, on the device (Alg. 1's del_num and fix_idx; Sec. 4.1's
+ * recent distance), so that a generation loop -- for instance one captured HIP graph replayed per token --
+ * needs no host arithmetic.  Call it once before every layer walk of a generated token; all arrays are
+ * DEVICE int32 [B] and are updated in place:
+ *   1. if pending_b[b] is set, the step prepared by the previous call has run: cache_len_b[b] grows by one
+ *      unless that step removed a row (evict_idx_b[b] >= 0); pending_b[b] is cleared
+ *   2. unless flush_only: n_seen_b[b] += 1; evict_idx_b[b] = ec_evict_index(n_seen_b[b], cache_len_b[b] + 1, ...)
+ *      with the budget / truncation arguments given here; new_pos_b[b] = n_seen_b[b] - 1; pending_b[b] = 1
+ * cache_len_b, evict_idx_b and new_pos_b are then what ec_decode_step_varlen takes for every layer of this
+ * token.  pending_b starts as zeros; call once more with flush_only = 1 after the last token so that
+ * cache_len_b holds the final lengths.
+ */
+int ec_retention_step_varlen(int32_t* n_seen_b, int32_t* cache_len_b, int32_t* evict_idx_b,
+                             int32_t* new_pos_b, int32_t* pending_b, int B, int gamma_num, int gamma_den,
+                             int budget_mode, int fixed_len, int trunc_mode, int recent, int n_tl,
+                             int protect_first, int flush_only, void* stream);
+
+/*
  * The "Frequency" discard policy of the generation stage -- the Frequency Cache of Sec. 4.1 Baselines that
  * the ablation of Table 3a ("Discard Position") compares the fixed-point elimination with: every cached
  * row carries the attention mass it has received, every generated token adds its attention row to it,

@@ -25,7 +25,7 @@ EC_MERGE_MEAN, EC_MERGE_EVICT = 0, 1
 SYMBOLS = ("ec_status_string", "ec_workspace_bytes", "ec_prefill_score", "ec_chunk_score", "ec_select_anchors",
            "ec_merge_compact", "ec_remerge_compact", "ec_evict_index", "ec_decode_step", "ec_decode_score_step",
            "ec_evict_min", "ec_prefill_score_varlen", "ec_select_anchors_varlen", "ec_merge_compact_varlen",
-           "ec_decode_step_varlen", "ec_importance_mean")
+           "ec_decode_step_varlen", "ec_importance_mean", "ec_retention_step_varlen")
 
 _lib = None
 
@@ -79,6 +79,8 @@ def load():
     lib.ec_decode_step_varlen.restype = c_int
     lib.ec_importance_mean.argtypes = [c_vp] + [c_int] * 4 + [c_vp]
     lib.ec_importance_mean.restype = c_int
+    lib.ec_retention_step_varlen.argtypes = [c_vp] * 5 + [c_int] * 10 + [c_vp]
+    lib.ec_retention_step_varlen.restype = c_int
     _lib = lib
     return lib
 
@@ -314,4 +316,19 @@ def ec_importance_mean(score, T_new: int, P: int = 0, check=True) -> int:
     rc = load().ec_importance_mean(_ptr(score, "score"), B, G, T_new, P, _stream())
     if check and rc != EC_OK:
         raise EcError("ec_importance_mean", rc)
+    return rc
+
+
+def ec_retention_step_varlen(n_seen_b, cache_len_b, evict_idx_b, new_pos_b, pending_b, gamma_num: int, gamma_den: int,
+                             budget_mode: int = EC_BUDGET_RATIO, fixed_len: int = 0, trunc_mode: int = EC_TRUNC_RECENT,
+                             recent: int = 25, n_tl: int = 0, protect_first: int = 1, flush_only: bool = False,
+                             check=True) -> int:
+    """Device-side retention test of a ragged batch; all arrays int32 [B] on the device, updated in place."""
+    B = n_seen_b.numel()
+    rc = load().ec_retention_step_varlen(_i32(n_seen_b, "n_seen_b", B), _i32(cache_len_b, "cache_len_b", B),
+                                         _i32(evict_idx_b, "evict_idx_b", B), _i32(new_pos_b, "new_pos_b", B),
+                                         _i32(pending_b, "pending_b", B), B, gamma_num, gamma_den, budget_mode, fixed_len,
+                                         trunc_mode, recent, n_tl, protect_first, 1 if flush_only else 0, _stream())
+    if check and rc != EC_OK:
+        raise EcError("ec_retention_step_varlen", rc)
     return rc

@@ -29,6 +29,9 @@ int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, 
                         float* head_imp, void* vt, int B, int H, ScoreGeom geo, const int32_t* seq_len, int D,
                         int dt, float scale, int forced_waves, hipStream_t stream);
 size_t score_mfma_vt_bytes(int B, int H, int T, int D);
+int retention_step_launch(int32_t* n_seen_b, int32_t* cache_len_b, int32_t* evict_idx_b, int32_t* new_pos_b,
+                          int32_t* pending_b, int B, int gamma_num, int gamma_den, int budget_mode, int fixed_len,
+                          int trunc_mode, int recent, int n_tl, int protect_first, int flush_only, hipStream_t stream);
 int importance_mean_launch(float* score, int B, int G, int Tq, int P, hipStream_t stream);
 int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, hipStream_t stream);
 }  // namespace ec
@@ -254,6 +257,22 @@ int ec_evict_index(int64_t n_seen, int len_after_append, int gamma_num, int gamm
     if (victim < protect_first) victim = protect_first;
     if (victim >= (int64_t)len_after_append - 1) return -1;
     return (int)victim;
+}
+
+int ec_retention_step_varlen(int32_t* n_seen_b, int32_t* cache_len_b, int32_t* evict_idx_b, int32_t* new_pos_b,
+                             int32_t* pending_b, int B, int gamma_num, int gamma_den, int budget_mode, int fixed_len,
+                             int trunc_mode, int recent, int n_tl, int protect_first, int flush_only, void* stream)
+{
+    if (!n_seen_b || !cache_len_b || !evict_idx_b || !new_pos_b || !pending_b || B < 1) return EC_EINVAL;
+    if (budget_mode != EC_BUDGET_RATIO && budget_mode != EC_BUDGET_FIXED) return EC_EINVAL;
+    if (trunc_mode != EC_TRUNC_RECENT && trunc_mode != EC_TRUNC_ABS) return EC_EINVAL;
+    if (budget_mode == EC_BUDGET_RATIO && (gamma_den < 1 || gamma_num < 0 || gamma_num > gamma_den)) return EC_EINVAL;
+    if (budget_mode == EC_BUDGET_FIXED && fixed_len < 1) return EC_EINVAL;
+    if (protect_first < 0 || (trunc_mode == EC_TRUNC_RECENT && recent < 0) || (trunc_mode == EC_TRUNC_ABS && n_tl < 0))
+        return EC_EINVAL;
+    return ec::retention_step_launch(n_seen_b, cache_len_b, evict_idx_b, new_pos_b, pending_b, B, gamma_num, gamma_den,
+                                     budget_mode, fixed_len, trunc_mode, recent, n_tl, protect_first, flush_only ? 1 : 0,
+                                     reinterpret_cast<hipStream_t>(stream));
 }
 
 int ec_decode_step(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,

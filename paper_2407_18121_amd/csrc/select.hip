@@ -149,4 +149,57 @@ int select_dispatch(const float* score, int B, int G, int T, int n_anchor, int p
     return status_from_hip(hipGetLastError());
 }
 
+// ------------------------------------------------------------------ retention test on the device
+// Per-sequence bookkeeping of a ragged generation loop (Alg. 1's del_num and fix_idx in integer arithmetic,
+// the same rules as the host function ec_evict_index), one thread per batch element.
+__global__ __launch_bounds__(256) void retention_step_kernel(int32_t* __restrict__ n_seen_b,
+                                                             int32_t* __restrict__ cache_len_b,
+                                                             int32_t* __restrict__ evict_idx_b,
+                                                             int32_t* __restrict__ new_pos_b,
+                                                             int32_t* __restrict__ pending_b, int B, int gamma_num,
+                                                             int gamma_den, int budget_mode, int fixed_len,
+                                                             int trunc_mode, int recent, int n_tl, int protect_first,
+                                                             int flush_only)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int len = cache_len_b[b];
+    if (pending_b[b]) {  // the step prepared by the previous call has run: a row was appended, maybe one removed
+        len += (evict_idx_b[b] < 0) ? 1 : 0;
+        pending_b[b] = 0;
+    }
+    if (!flush_only) {
+        const long long seen = (long long)n_seen_b[b] + 1;
+        const long long after = (long long)len + 1;
+        long long keep;
+        if (budget_mode == EC_BUDGET_RATIO) {
+            const long long prod = (long long)gamma_num * seen;
+            keep = prod / gamma_den + ((prod % gamma_den) ? 1 : 0);
+        } else {
+            keep = fixed_len;
+        }
+        long long victim = -1;
+        if (after > keep) {
+            victim = (trunc_mode == EC_TRUNC_RECENT) ? after - 1 - recent : (long long)n_tl;
+            if (victim < protect_first) victim = protect_first;
+            if (victim >= after - 1) victim = -1;
+        }
+        n_seen_b[b] = (int32_t)seen;
+        evict_idx_b[b] = (int32_t)victim;
+        new_pos_b[b] = (int32_t)(seen - 1);
+        pending_b[b] = 1;
+    }
+    cache_len_b[b] = len;
+}
+
+int retention_step_launch(int32_t* n_seen_b, int32_t* cache_len_b, int32_t* evict_idx_b, int32_t* new_pos_b,
+                          int32_t* pending_b, int B, int gamma_num, int gamma_den, int budget_mode, int fixed_len,
+                          int trunc_mode, int recent, int n_tl, int protect_first, int flush_only, hipStream_t stream)
+{
+    hipLaunchKernelGGL(retention_step_kernel, dim3((B + 255) / 256), dim3(256), 0, stream, n_seen_b, cache_len_b,
+                       evict_idx_b, new_pos_b, pending_b, B, gamma_num, gamma_den, budget_mode, fixed_len, trunc_mode,
+                       recent, n_tl, protect_first, flush_only);
+    return status_from_hip(hipGetLastError());
+}
+
 }  // namespace ec

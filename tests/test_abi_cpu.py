@@ -68,6 +68,11 @@ def test_invalid_arguments_are_rejected_before_any_launch():
     assert lib.ec_decode_score_step(one, one, one, one, one, None, one, 1, 1, 1, 64, 8, 3, 0, 1.0, 0, one, one, 16, None) == ec.EC_EWORKSPACE
     assert lib.ec_evict_min(one, one, None, one, 1, 1, 1, 64, 8, 3, 2, 1, 0, one, None) == ec.EC_EINVAL   # nothing left to choose from
     assert lib.ec_evict_min(one, one, None, one, 1, 1, 1, 64, 8, 9, 1, 1, 0, one, None) == ec.EC_EINVAL   # len > cap
+    assert lib.ec_retention_step_varlen(one, one, one, one, None, 4, 1, 2, 0, 0, 0, 25, 0, 1, 0, None) == ec.EC_EINVAL  # no pending_b
+    assert lib.ec_retention_step_varlen(one, one, one, one, one, 4, 3, 2, 0, 0, 0, 25, 0, 1, 0, None) == ec.EC_EINVAL   # gamma > 1
+    assert lib.ec_retention_step_varlen(one, one, one, one, one, 4, 1, 2, 1, 0, 0, 25, 0, 1, 0, None) == ec.EC_EINVAL   # fixed_len < 1
+    assert lib.ec_importance_mean(None, 1, 1, 8, 0, None) == ec.EC_EINVAL
+    assert lib.ec_importance_mean(one, 1, 1, 0, 0, None) == ec.EC_EINVAL
 
 
 def test_evict_index_matches_oracle_everywhere():

@@ -81,10 +81,10 @@ def test_graph_replays_match_eager(dtype, D):
 
 
 def test_ragged_generation_loop_runs_from_one_graph_without_the_host():
-    """One captured graph = one generated token of a ragged batch: the retention test (Alg. 1's del_num, the
-    recent-distance victim of Sec. 4.1) runs as device integer arithmetic, ec_decode_step_varlen reads the
-    per-sequence numbers from device memory, and the lengths are updated on the device.  Replaying it must
-    equal the eager loop in which the host computes every index with ec_evict_index."""
+    """One captured graph = one generated token of a ragged batch: ec_retention_step_varlen runs the retention
+    test (Alg. 1's del_num, the recent-distance victim of Sec. 4.1) and the length bookkeeping on the device and
+    ec_decode_step_varlen reads the per-sequence numbers from device memory.  Replaying it must equal the eager
+    loop in which the host computes every index with ec_evict_index."""
     dtype, B, H, D, steps, recent, pf = "bf16", 3, 4, 128, 30, 25, 1
     p, qd = 1, 4
     prompt = [160, 300, 480]
@@ -120,21 +120,17 @@ def test_ragged_generation_loop_runs_from_one_graph_without_the_host():
     q_in, k_in, v_in = (torch.zeros((B, H, D), dtype=torch.bfloat16, device="cuda") for _ in range(3))
     g_out = torch.zeros((B, H, D), dtype=torch.bfloat16, device="cuda")
 
+    g_pending = torch.zeros(B, dtype=torch.int32, device="cuda")
+
     def one_token():
-        g_seen.add_(1)
-        keep = (g_seen * p + (qd - 1)) // qd                    # ceil(gamma * tokens seen)
-        vic = torch.clamp_min(g_len - recent, pf)               # (len + 1) - 1 - recent, raised to protect_first
-        go = ((g_len + 1) > keep) & (vic < g_len)
-        g_vic.copy_(torch.where(go, vic, torch.full_like(vic, -1)).to(torch.int32))
-        g_newpos.copy_((g_seen - 1).to(torch.int32))
+        ec.ec_retention_step_varlen(g_seen, g_len, g_vic, g_newpos, g_pending, p, qd, recent=recent, protect_first=pf)
         ec.ec_decode_step_varlen(q_in, k_in, v_in, g_kc, g_vc, g_pos, g_len, g_vic, g_newpos, 0.088, g_out)
-        g_len.add_((~go).to(torch.int32))
 
     # warm-up on throw-away state, then capture
-    saved = [t.clone() for t in (g_kc, g_vc, g_pos, g_len, g_seen)]
+    saved = [t.clone() for t in (g_kc, g_vc, g_pos, g_len, g_seen, g_pending)]
     one_token()
     torch.cuda.synchronize()
-    for t, s_ in zip((g_kc, g_vc, g_pos, g_len, g_seen), saved):
+    for t, s_ in zip((g_kc, g_vc, g_pos, g_len, g_seen, g_pending), saved):
         t.copy_(s_)
     g = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
@@ -144,12 +140,14 @@ def test_ragged_generation_loop_runs_from_one_graph_without_the_host():
             one_token()
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
-    for t, s_ in zip((g_kc, g_vc, g_pos, g_len, g_seen), saved):   # capture does not execute, but be explicit
+    for t, s_ in zip((g_kc, g_vc, g_pos, g_len, g_seen, g_pending), saved):   # capture does not execute, but be explicit
         t.copy_(s_)
     for s in range(steps):
         q_in.copy_(dq[s]); k_in.copy_(dk[s]); v_in.copy_(dv[s])
         g.replay()
         assert torch.equal(g_out, outs[s]), s
+    ec.ec_retention_step_varlen(g_seen, g_len, g_vic, g_newpos, g_pending, p, qd, recent=recent, protect_first=pf,
+                                flush_only=True)
     torch.cuda.synchronize()
     assert g_len.cpu().tolist() == lens
     for b in range(B):

@@ -151,3 +151,27 @@ def test_ragged_with_equal_lengths_is_the_dense_call():
         res.append((out, score, idx, kc, vc))
     for a, b in zip(*res):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("budget_mode,trunc_mode", [(0, 0), (1, 0), (0, 1), (1, 1)])
+def test_retention_step_on_the_device_matches_the_oracle(budget_mode, trunc_mode):
+    """ec_retention_step_varlen = the oracle's retention test for every sequence, step after step (bit-exact)."""
+    prompts = [1, 7, 60, 160, 300, 481, 1000, 5000, 26, 27]
+    B = len(prompts)
+    p, q = 3, 7
+    lens = [max(1, -(-p * t // q)) for t in prompts]
+    kw = dict(budget_mode=budget_mode, fixed_len=40, trunc_mode=trunc_mode, recent=25, n_tl=9, protect_first=1)
+    n_seen, length = _i32(prompts), _i32(lens)
+    evict, new_pos, pending = (torch.zeros(B, dtype=torch.int32, device="cuda") for _ in range(3))
+    o_seen, o_len = list(prompts), list(lens)
+    for step in range(80):
+        ec.ec_retention_step_varlen(n_seen, length, evict, new_pos, pending, p, q, **kw)
+        o_seen = [n + 1 for n in o_seen]
+        o_vic = [oracle.evict_index(o_seen[b], o_len[b] + 1, p, q, **kw) for b in range(B)]
+        torch.cuda.synchronize()
+        assert n_seen.cpu().tolist() == o_seen and evict.cpu().tolist() == o_vic, step
+        assert length.cpu().tolist() == o_len and new_pos.cpu().tolist() == [n - 1 for n in o_seen], step
+        o_len = [n + (0 if v >= 0 else 1) for n, v in zip(o_len, o_vic)]
+    ec.ec_retention_step_varlen(n_seen, length, evict, new_pos, pending, p, q, flush_only=True, **kw)
+    torch.cuda.synchronize()
+    assert length.cpu().tolist() == o_len and n_seen.cpu().tolist() == o_seen and pending.cpu().tolist() == [0] * B
