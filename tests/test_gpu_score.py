@@ -70,3 +70,20 @@ def test_importance_mean_metric(B, G, Tq, P):
     ec.ec_importance_mean(d, Tq, P)
     torch.cuda.synchronize()
     np.testing.assert_allclose(d.cpu().numpy().astype(np.float64), ref, rtol=3e-7, atol=0)   # one fp32 division
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
+def test_peaked_and_flat_attention(dtype, D):
+    """Scores hundreds of units apart (softmax one-hot to fp32 precision) and all-equal scores (uniform rows)."""
+    cfg = syn.custom("t", H=2, D=D, B=1, T=300, dtype=dtype, cid=8080)
+    q, k, v = syn.prompt_qkv(cfg)
+    from util import quantize
+    for gain, scale in ((6.0, 1.0), (0.0, 1.0)):
+        qq = quantize(q * gain, dtype)
+        ref = oracle.prefill_score(qq, k, v, scale, 1)
+        out, lse, score = run_gpu_score(qq, k, v, dtype, scale, 1)
+        assert np.isfinite(out).all() and np.isfinite(lse).all() and np.isfinite(score).all()
+        assert_close(out, ref["out"], dtype, f"out gain {gain}")
+        assert_close(score, ref["score"], dtype, f"score gain {gain}")
+        # the log-sum-exp itself is hundreds of units large here: compare relative to its size
+        np.testing.assert_allclose(lse, ref["lse"], rtol=2e-6 if dtype == "f32" else 1e-5, atol=2e-2 if dtype == "bf16" else 1e-4)
