@@ -33,7 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 FP32_VALU_PEAK_TFLOPS = 157.3
 # HBM bytes actually moved per algorithmic byte, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/decode_step_hbm_traffic.txt (counters scaled by a 256 MiB device copy in the same run)
-DECODE_TRAFFIC_RATIO = {"C2": 1.04, "C5": 1.03}
+DECODE_TRAFFIC_RATIO = {"C2": 1.04, "C3": 1.04, "C4": 1.03, "C5": 1.03}
 
 
 def parse():
