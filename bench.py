@@ -34,6 +34,7 @@ FP32_VALU_PEAK_TFLOPS = 157.3
 # HBM bytes actually moved per algorithmic byte, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/decode_step_hbm_traffic.txt (counters scaled by a 256 MiB device copy in the same run)
 DECODE_TRAFFIC_RATIO = {"C2": 1.04, "C3": 1.04, "C4": 1.03, "C5": 1.03}
+PROMPT_BUDGET_GB = 160       # HBM set aside for the prompts' Q, K, V (of 288 GB)
 
 
 def parse():
@@ -41,7 +42,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "T1", "T2", "T3", "T4"])
+    ap.add_argument("--config", default="C5", choices=["C1", "C2", "C3", "C4", "C5", "T1", "T2", "T3", "T4"],
+                    help="workload (default C5: the largest single-GPU one, on which the roofline bars are defined)")
     ap.add_argument("--score-mode", default="layer", choices=["layer", "head"])
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -59,7 +61,8 @@ def parse():
                     help="only the main step: no second turn, frequency policy, ragged or layers-folded runs "
                          "(kernel traces then hold the main path's launches alone)")
     ap.add_argument("--distinct-layers", type=int, default=0,
-                    help="distinct prompt tensors to generate (0 = one per layer; fewer are cycled)")
+                    help="distinct prompt tensors to generate (0 = one per layer, or as many as fit in "
+                         f"{PROMPT_BUDGET_GB} GB of HBM; fewer than the layers are cycled, and the JSON line says so)")
     args = ap.parse_args()
     if args.no_extras:
         args.turn2 = args.freq_steps = args.ragged_steps = 0
@@ -79,7 +82,10 @@ class Workload:
         self.dt_code = ec.EC_F32 if cfg.dtype == "f32" else ec.EC_BF16
         B, H, T, D, L = cfg.B, cfg.H, cfg.T, cfg.D, cfg.layers
         self.G = 1 if score_mode == "layer" else H
-        n_distinct = L if distinct_layers <= 0 else min(L, distinct_layers)
+        per_layer = 3.0 * B * H * T * D * cfg.esize
+        fit = max(1, int(PROMPT_BUDGET_GB * 1e9 // per_layer))
+        n_distinct = min(L, fit) if distinct_layers <= 0 else min(L, distinct_layers)
+        self.n_distinct = n_distinct
         self.prompts = [synt.prompt_qkv_device(cfg, l) for l in range(n_distinct)]
         self.dec = [synt.decode_stream_device(cfg, l) for l in range(L)]
         cap, nA, G = cfg.cap, cfg.n_anchor, self.G
@@ -579,7 +585,7 @@ def main():
         "config": {"workload": f"{cfg.name}: {L} layers, {cfg.H} heads, head_dim {cfg.D}, batch {B}, prompt {cfg.T}, "
                                f"budget {cfg.gamma[0]}/{cfg.gamma[1]}, {cfg.decode_steps} decode steps, {cfg.dtype}",
                    "score_mode": args.score_mode, "launch": "hipgraph" if use_graph else "eager", "truncated_decode": truncated,
-                   "cache_len": [cfg.n_anchor, wl.final_len]},
+                   "cache_len": [cfg.n_anchor, wl.final_len], "distinct_prompt_layers": wl.n_distinct},
         "detail": {
             "decode_attn_GBps": dec_gbps, "decode_tokens_per_s": B * cfg.decode_steps / (decode_ms * 1e-3),
             "decode_us_per_launch": dec_launch_us, "decode_launches": n_dec,
@@ -596,6 +602,8 @@ def main():
             "kernel": "decode_step_kernel", "bound": "hbm", "achieved": dec_gbps, "peak": HBM_PEAK_GBPS,
             "unit": "GB/s", "frac": dec_gbps / HBM_PEAK_GBPS,
             "traffic": (DECODE_TRAFFIC_RATIO[cfg.name] * wl.decode_bytes / n_dec) if cfg.name in DECODE_TRAFFIC_RATIO else None,
+            "traffic_source": "algorithmic bytes of this run x the FETCH_SIZE+WRITE_SIZE / algorithmic ratio of the "
+                              "rocprofv3 --pmc runs in profiles/decode_step_hbm_traffic.txt",
             "bytes_per_launch": wl.decode_bytes / n_dec, "us_per_launch": dec_launch_us,
             "frac_of_measured_copy": dec_gbps / copy_gbps,
         },

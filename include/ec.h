@@ -90,7 +90,7 @@ size_t ec_workspace_bytes(int fn, int B, int H, int T, int D, int dt);
  *     I_n   = sum_{m>=n} A_mn                                    (column mass)
  * score[b,g,n] = I_n of head g when G == H, or the mean of I_n over the H heads
  * when G == 1 (the paper's layer-wise metric).  scale = 1 gives Eq. 1 literally;
- * models use 1/sqrt(D).
+ * models use 1/sqrt(D).  scale must be finite and > 0 (else EC_EINVAL).
  *   q,k,v  DEVICE [B,H,T,D] dt, read only
  *   out    DEVICE [B,H,T,D] dt, written; may be NULL (attention output not wanted)
  *   lse    DEVICE [B,H,T] float, written; may be NULL (kept in ws instead)
@@ -130,8 +130,10 @@ int ec_chunk_score(const void* q, const void* k, const void* v, void* out, float
                    void* ws, size_t ws_bytes, void* stream);
 
 /*
- * The "Mean" importance metric of the ablation on the importance metric (Table 3d), from the "Sum" the
- * scoring calls emit: every score is divided, in place, by the number of queries that can see its row.
+ * A "Mean" importance metric in the sense of the ablation on the importance metric (Table 3d), from the
+ * "Sum" the scoring calls emit.  The paper names the metric but prints no formula for it; the definition
+ * here is this library's own reading: every score is divided, in place, by the number of queries that can
+ * see its row.
  * After ec_prefill_score pass T_new = T, P = 0 (row n is seen by T - n queries); after ec_chunk_score pass
  * its T_new and P (row n is seen by T_new - max(0, n - P) queries).
  *   score  DEVICE [B,G,P+T_new] float, updated in place
@@ -139,8 +141,8 @@ int ec_chunk_score(const void* q, const void* k, const void* v, void* out, float
 int ec_importance_mean(float* score, int B, int G, int T_new, int P, void* stream);
 
 /*
- * Anchor selection (Sec. 3.3: "top N_I tokens in I_n, indices in ascending
- * order"; Sec. 4.1: the first and the most recent token are protected).
+ * Anchor selection (Sec. 3.3: the N_I positions of largest importance, listed in
+ * ascending position; Sec. 4.1: the first and the most recent token are protected).
  * For every (b,g): positions 0..protect_first-1 and T-protect_last..T-1 are
  * always selected; of the others the n_anchor - protect_first - protect_last
  * with the largest score are selected, equal scores going to the lower position.
@@ -236,15 +238,34 @@ int ec_evict_index(int64_t n_seen, int len_after_append, int gamma_num, int gamm
  *   pos               DEVICE [B,G,cap] int32 original position of every row, updated
  *                     like the cache; may be NULL
  *   out               DEVICE [B,H,D] dt, written
- *   ws                reserved: ec_workspace_bytes(EC_FN_DECODE_STEP, ...) is 0 and ws may be
- *                     NULL (one workgroup owns a whole (batch, head); nothing is staged)
- * Requires 0 <= cache_len < cap and -1 <= evict_idx <= cache_len.  Dot products
- * and the softmax are evaluated in fp32.
+ *   ws                DEVICE scratch, optional.  With ec_workspace_bytes(EC_FN_DECODE_STEP, B,H,cap,D,dt)
+ *                     bytes (0 when B*H alone fills the chip) the rows of one (batch, head) may be
+ *                     divided over several workgroups whose partial results meet in ws and are
+ *                     merged by a second launch on the same stream; with ws NULL or smaller, one
+ *                     workgroup streams a whole (batch, head) and nothing is staged.  Both shapes
+ *                     compute the same function; cache moves are bit-exact in both.
+ * Requires 0 <= cache_len < cap, -1 <= evict_idx <= cache_len and a finite scale > 0.  Dot
+ * products and the softmax are evaluated in fp32.
  */
 int ec_decode_step(const void* q, const void* k_new, const void* v_new, void* k_cache,
                    void* v_cache, int32_t* pos, int B, int H, int G, int D, int cap, int cache_len,
                    int evict_idx, int32_t new_pos, float scale, int dt, void* out, void* ws,
                    size_t ws_bytes, void* stream);
+
+/*
+ * ec_decode_step with an explicit launch shape, for tests and tuning sweeps (the library reads no
+ * environment variable and keeps no state: a shape other than its own choice is requested here).
+ *   waves   wavefronts per workgroup (0 = the library's choice)
+ *   unroll  16-byte loads of K and of V each lane keeps in flight (0 = the library's choice)
+ *   splits  workgroups per (batch, head): 0 = the library's choice, 1 = one workgroup and no
+ *           workspace, n > 1 = n workgroups plus the merging launch; ws must then hold
+ *           4 * B * H * n * (D + 2) bytes, else EC_EWORKSPACE
+ * Combinations the library has no kernel for return EC_EINVAL.  Everything else as ec_decode_step.
+ */
+int ec_decode_step_shaped(const void* q, const void* k_new, const void* v_new, void* k_cache,
+                          void* v_cache, int32_t* pos, int B, int H, int G, int D, int cap,
+                          int cache_len, int evict_idx, int32_t new_pos, float scale, int dt, void* out,
+                          void* ws, size_t ws_bytes, int waves, int unroll, int splits, void* stream);
 
 /*
  * Ragged batches: the same four steps for a batch whose sequences differ in length (what a serving

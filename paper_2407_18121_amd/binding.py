@@ -25,7 +25,7 @@ EC_MERGE_MEAN, EC_MERGE_EVICT = 0, 1
 SYMBOLS = ("ec_status_string", "ec_workspace_bytes", "ec_prefill_score", "ec_chunk_score", "ec_select_anchors",
            "ec_merge_compact", "ec_remerge_compact", "ec_evict_index", "ec_decode_step", "ec_decode_score_step",
            "ec_evict_min", "ec_prefill_score_varlen", "ec_select_anchors_varlen", "ec_merge_compact_varlen",
-           "ec_decode_step_varlen", "ec_importance_mean", "ec_retention_step_varlen")
+           "ec_decode_step_varlen", "ec_importance_mean", "ec_retention_step_varlen", "ec_decode_step_shaped")
 
 _lib = None
 
@@ -65,6 +65,9 @@ def load():
     lib.ec_evict_index.restype = c_int
     lib.ec_decode_step.argtypes = ([c_vp] * 6 + [c_int] * 7 + [ctypes.c_int32, c_f, c_int, c_vp, c_vp, c_sz, c_vp])
     lib.ec_decode_step.restype = c_int
+    lib.ec_decode_step_shaped.argtypes = ([c_vp] * 6 + [c_int] * 7 + [ctypes.c_int32, c_f, c_int, c_vp, c_vp, c_sz]
+                                          + [c_int] * 3 + [c_vp])
+    lib.ec_decode_step_shaped.restype = c_int
     lib.ec_decode_score_step.argtypes = ([c_vp] * 7 + [c_int] * 6 + [ctypes.c_int32, c_f, c_int, c_vp, c_vp, c_sz, c_vp])
     lib.ec_decode_score_step.restype = c_int
     lib.ec_evict_min.argtypes = [c_vp] * 4 + [c_int] * 9 + [c_vp, c_vp]
@@ -107,6 +110,49 @@ def _ptr(t, name="tensor"):
     return t.data_ptr()
 
 
+def _chk(t, name, dtype, shape, optional=False):
+    """Pointer of a tensor after checking what the C ABI cannot: element type, shape, device, layout.
+    A wrong type or shape would make a kernel read or write out of bounds."""
+    if t is None:
+        if optional:
+            return None
+        raise ValueError(f"{name} is required")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    return _Checked(t, name)
+
+
+class _Checked:
+    """A tensor whose type and shape fit; its device and layout are checked when the pointer is taken, after
+    every argument of the call has passed the type and shape checks."""
+    __slots__ = ("t", "name")
+
+    def __init__(self, t, name):
+        self.t, self.name = t, name
+
+
+def _call(fn, *args):
+    """Call a library function; _Checked arguments become device pointers here, and the stream (passed as the
+    function that looks it up) is resolved last, once every tensor has been found in device memory."""
+    ptrs = [_ptr(a.t, a.name) if isinstance(a, _Checked) else a for a in args]
+    return fn(*[a() if callable(a) else a for a in ptrs])
+
+
+def _ws(ws):
+    """(pointer, bytes) of an optional workspace tensor."""
+    if ws is None:
+        return None, 0
+    return _Checked(ws, "ws"), ws.numel() * ws.element_size()
+
+
+def _groups(G, H, what):
+    if G != 1 and G != H:
+        raise ValueError(f"{what}: the number of score groups must be 1 or H={H}, got {G}")
+    return G
+
+
 def _stream():
     return torch.cuda.current_stream().cuda_stream
 
@@ -125,11 +171,16 @@ def new_workspace(fn: int, B: int, H: int, T: int, D: int, dt: int, device="cuda
 
 def ec_prefill_score(q, k, v, out, lse, score, scale: float, ws, check=True) -> int:
     """q,k,v [B,H,T,D]; out [B,H,T,D] or None; lse [B,H,T] f32 or None; score [B,G,T] f32."""
+    if q.dim() != 4 or score.dim() != 3:
+        raise ValueError("ec_prefill_score: q must be [B,H,T,D] and score [B,G,T]")
     B, H, T, D = q.shape
-    G = score.shape[1]
-    rc = load().ec_prefill_score(_ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(out, "out"), _ptr(lse, "lse"),
-                                 _ptr(score, "score"), B, H, G, T, D, dtype_code(q), scale, _ptr(ws, "ws"),
-                                 0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    G = _groups(score.shape[1], H, "ec_prefill_score")
+    dt, f32 = q.dtype, torch.float32
+    wp, wb = _ws(ws)
+    rc = _call(load().ec_prefill_score, _chk(q, "q", dt, (B, H, T, D)), _chk(k, "k", dt, (B, H, T, D)),
+                                 _chk(v, "v", dt, (B, H, T, D)), _chk(out, "out", dt, (B, H, T, D), True),
+                                 _chk(lse, "lse", f32, (B, H, T), True), _chk(score, "score", f32, (B, G, T)),
+                                 B, H, G, T, D, dtype_code(q), scale, wp, wb, _stream)
     if check and rc != EC_OK:
         raise EcError("ec_prefill_score", rc)
     return rc
@@ -137,14 +188,18 @@ def ec_prefill_score(q, k, v, out, lse, score, scale: float, ws, check=True) -> 
 
 def ec_chunk_score(q, k, v, P: int, out, lse, score, scale: float, ws, check=True) -> int:
     """q [B,H,T_new,D]; k,v [B,H,kv_rows,D] holding P cached rows then the chunk's rows; score [B,G,P+T_new]."""
+    if q.dim() != 4 or k.dim() != 4 or score.dim() != 3:
+        raise ValueError("ec_chunk_score: q, k must be 4-D and score 3-D")
     B, H, T_new, D = q.shape
     kv_rows = k.shape[2]
-    G = score.shape[1]
-    if k.shape != v.shape or k.shape[:2] != q.shape[:2] or k.shape[3] != D or score.shape[2] != P + T_new:
-        raise ValueError("ec_chunk_score: inconsistent shapes")
-    rc = load().ec_chunk_score(_ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(out, "out"), _ptr(lse, "lse"),
-                               _ptr(score, "score"), B, H, G, T_new, P, kv_rows, D, dtype_code(q), scale,
-                               _ptr(ws, "ws"), 0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    G = _groups(score.shape[1], H, "ec_chunk_score")
+    dt, f32 = q.dtype, torch.float32
+    wp, wb = _ws(ws)
+    rc = _call(load().ec_chunk_score, _chk(q, "q", dt, (B, H, T_new, D)), _chk(k, "k", dt, (B, H, kv_rows, D)),
+                               _chk(v, "v", dt, (B, H, kv_rows, D)), _chk(out, "out", dt, (B, H, T_new, D), True),
+                               _chk(lse, "lse", f32, (B, H, T_new), True),
+                               _chk(score, "score", f32, (B, G, P + T_new)), B, H, G, T_new, P, kv_rows, D,
+                               dtype_code(q), scale, wp, wb, _stream)
     if check and rc != EC_OK:
         raise EcError("ec_chunk_score", rc)
     return rc
@@ -152,9 +207,12 @@ def ec_chunk_score(q, k, v, P: int, out, lse, score, scale: float, ws, check=Tru
 
 def ec_select_anchors(score, n_anchor: int, protect_first: int, protect_last: int, anchor_idx, check=True) -> int:
     """score [B,G,T] f32 -> anchor_idx [B,G,n_anchor] int32 ascending."""
+    if score.dim() != 3:
+        raise ValueError("ec_select_anchors: score must be [B,G,T]")
     B, G, T = score.shape
-    rc = load().ec_select_anchors(_ptr(score, "score"), B, G, T, n_anchor, protect_first, protect_last,
-                                  _ptr(anchor_idx, "anchor_idx"), None, 0, _stream())
+    rc = _call(load().ec_select_anchors, _chk(score, "score", torch.float32, (B, G, T)), B, G, T, n_anchor, protect_first,
+                                  protect_last, _chk(anchor_idx, "anchor_idx", torch.int32, (B, G, n_anchor)), None, 0,
+                                  _stream)
     if check and rc != EC_OK:
         raise EcError("ec_select_anchors", rc)
     return rc
@@ -163,12 +221,19 @@ def ec_select_anchors(score, n_anchor: int, protect_first: int, protect_last: in
 def ec_merge_compact(k, v, anchor_idx, k_cache, v_cache, counts=None, assign=None, pos=None,
                      merge_mode: int = EC_MERGE_MEAN, check=True) -> int:
     """k,v [B,H,T,D]; anchor_idx [B,G,n]; k_cache,v_cache [B,H,cap,D]."""
+    if k.dim() != 4 or anchor_idx.dim() != 3 or k_cache.dim() != 4:
+        raise ValueError("ec_merge_compact: k, k_cache must be 4-D and anchor_idx 3-D")
     B, H, T, D = k.shape
-    G, n_anchor = anchor_idx.shape[1], anchor_idx.shape[2]
+    G, n_anchor = _groups(anchor_idx.shape[1], H, "ec_merge_compact"), anchor_idx.shape[2]
     cap = k_cache.shape[2]
-    rc = load().ec_merge_compact(_ptr(k, "k"), _ptr(v, "v"), _ptr(anchor_idx, "anchor_idx"), B, H, G, T, D, n_anchor,
-                                 dtype_code(k), merge_mode, _ptr(k_cache, "k_cache"), _ptr(v_cache, "v_cache"), cap,
-                                 _ptr(counts, "counts"), _ptr(assign, "assign"), _ptr(pos, "pos"), _stream())
+    dt, i32 = k.dtype, torch.int32
+    rc = _call(load().ec_merge_compact, _chk(k, "k", dt, (B, H, T, D)), _chk(v, "v", dt, (B, H, T, D)),
+                                 _chk(anchor_idx, "anchor_idx", i32, (B, G, n_anchor)), B, H, G, T, D, n_anchor,
+                                 dtype_code(k), merge_mode, _chk(k_cache, "k_cache", dt, (B, H, cap, D)),
+                                 _chk(v_cache, "v_cache", dt, (B, H, cap, D)), cap,
+                                 _chk(counts, "counts", i32, (B, G, n_anchor), True),
+                                 _chk(assign, "assign", i32, (B, G, T), True), _chk(pos, "pos", i32, (B, G, cap), True),
+                                 _stream)
     if check and rc != EC_OK:
         raise EcError("ec_merge_compact", rc)
     return rc
@@ -177,17 +242,21 @@ def ec_merge_compact(k, v, anchor_idx, k_cache, v_cache, counts=None, assign=Non
 def ec_remerge_compact(k, v, L: int, anchor_idx, k_cache, v_cache, weights=None, src_pos=None, counts=None,
                        assign=None, pos=None, merge_mode: int = EC_MERGE_MEAN, check=True) -> int:
     """k,v [B,H,src_rows,D] of which rows 0..L-1 are merged; weights, src_pos [B,G,L] int32 or None."""
+    if k.dim() != 4 or anchor_idx.dim() != 3 or k_cache.dim() != 4:
+        raise ValueError("ec_remerge_compact: k, k_cache must be 4-D and anchor_idx 3-D")
     B, H, src_rows, D = k.shape
-    G, n_anchor = anchor_idx.shape[1], anchor_idx.shape[2]
+    G, n_anchor = _groups(anchor_idx.shape[1], H, "ec_remerge_compact"), anchor_idx.shape[2]
     cap = k_cache.shape[2]
-    for name, t in (("weights", weights), ("src_pos", src_pos)):
-        if t is not None and tuple(t.shape) != (B, G, L):
-            raise ValueError(f"ec_remerge_compact: {name} must be [B,G,L]")
-    rc = load().ec_remerge_compact(_ptr(k, "k"), _ptr(v, "v"), src_rows, _ptr(weights, "weights"),
-                                   _ptr(src_pos, "src_pos"), _ptr(anchor_idx, "anchor_idx"), B, H, G, L, D,
-                                   n_anchor, dtype_code(k), merge_mode, _ptr(k_cache, "k_cache"),
-                                   _ptr(v_cache, "v_cache"), cap, _ptr(counts, "counts"), _ptr(assign, "assign"),
-                                   _ptr(pos, "pos"), _stream())
+    dt, i32 = k.dtype, torch.int32
+    rc = _call(load().ec_remerge_compact, _chk(k, "k", dt, (B, H, src_rows, D)), _chk(v, "v", dt, (B, H, src_rows, D)),
+                                   src_rows, _chk(weights, "weights", i32, (B, G, L), True),
+                                   _chk(src_pos, "src_pos", i32, (B, G, L), True),
+                                   _chk(anchor_idx, "anchor_idx", i32, (B, G, n_anchor)), B, H, G, L, D, n_anchor,
+                                   dtype_code(k), merge_mode, _chk(k_cache, "k_cache", dt, (B, H, cap, D)),
+                                   _chk(v_cache, "v_cache", dt, (B, H, cap, D)), cap,
+                                   _chk(counts, "counts", i32, (B, G, n_anchor), True),
+                                   _chk(assign, "assign", i32, (B, G, L), True),
+                                   _chk(pos, "pos", i32, (B, G, cap), True), _stream)
     if check and rc != EC_OK:
         raise EcError("ec_remerge_compact", rc)
     return rc
@@ -203,30 +272,56 @@ def ec_evict_index(n_seen: int, len_after_append: int, gamma_num: int, gamma_den
     return int(r)
 
 
-def ec_decode_step(q, k_new, v_new, k_cache, v_cache, pos, cache_len: int, evict_idx: int, new_pos: int,
-                   scale: float, out, ws, G: int | None = None, check=True) -> int:
-    """q,k_new,v_new,out [B,H,D]; k_cache,v_cache [B,H,cap,D]; pos [B,G,cap] int32 or None."""
+def _decode_args(q, k_new, v_new, k_cache, v_cache, pos, out, G, what):
+    """Checked pointers of the tensors every generation-step call takes."""
+    if k_cache.dim() != 4:
+        raise ValueError(f"{what}: k_cache must be [B,H,cap,D]")
     B, H, cap, D = k_cache.shape
     if G is None:
         G = pos.shape[1] if pos is not None else 1
-    rc = load().ec_decode_step(_ptr(q, "q"), _ptr(k_new, "k_new"), _ptr(v_new, "v_new"), _ptr(k_cache, "k_cache"),
-                               _ptr(v_cache, "v_cache"), _ptr(pos, "pos"), B, H, G, D, cap, cache_len, evict_idx,
-                               new_pos, scale, dtype_code(k_cache), _ptr(out, "out"), _ptr(ws, "ws"),
-                               0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    _groups(G, H, what)
+    dt = k_cache.dtype
+    ptrs = (_chk(q, "q", dt, (B, H, D)), _chk(k_new, "k_new", dt, (B, H, D)), _chk(v_new, "v_new", dt, (B, H, D)),
+            _chk(k_cache, "k_cache", dt, (B, H, cap, D)), _chk(v_cache, "v_cache", dt, (B, H, cap, D)),
+            _chk(pos, "pos", torch.int32, (B, G, cap), True))
+    return ptrs, _chk(out, "out", dt, (B, H, D)), (B, H, G, D, cap)
+
+
+def ec_decode_step(q, k_new, v_new, k_cache, v_cache, pos, cache_len: int, evict_idx: int, new_pos: int,
+                   scale: float, out, ws, G: int | None = None, check=True) -> int:
+    """q,k_new,v_new,out [B,H,D]; k_cache,v_cache [B,H,cap,D]; pos [B,G,cap] int32 or None."""
+    ptrs, po, (B, H, G, D, cap) = _decode_args(q, k_new, v_new, k_cache, v_cache, pos, out, G, "ec_decode_step")
+    wp, wb = _ws(ws)
+    rc = _call(load().ec_decode_step, *ptrs, B, H, G, D, cap, cache_len, evict_idx, new_pos, scale, dtype_code(k_cache), po,
+                               wp, wb, _stream)
     if check and rc != EC_OK:
         raise EcError("ec_decode_step", rc)
+    return rc
+
+
+def ec_decode_step_shaped(q, k_new, v_new, k_cache, v_cache, pos, cache_len: int, evict_idx: int, new_pos: int,
+                          scale: float, out, ws, waves: int = 0, unroll: int = 0, splits: int = 0,
+                          G: int | None = None, check=True) -> int:
+    """ec_decode_step with an explicit launch shape (tests and tuning sweeps)."""
+    ptrs, po, (B, H, G, D, cap) = _decode_args(q, k_new, v_new, k_cache, v_cache, pos, out, G, "ec_decode_step_shaped")
+    wp, wb = _ws(ws)
+    rc = _call(load().ec_decode_step_shaped, *ptrs, B, H, G, D, cap, cache_len, evict_idx, new_pos, scale,
+                                      dtype_code(k_cache), po, wp, wb, waves, unroll, splits, _stream)
+    if check and rc != EC_OK:
+        raise EcError("ec_decode_step_shaped", rc)
     return rc
 
 
 def ec_decode_score_step(q, k_new, v_new, k_cache, v_cache, pos, freq, cache_len: int, new_pos: int, scale: float,
                          out, ws, check=True) -> int:
     """Frequency policy: append + attend + add the attention row to freq [B,G,cap] f32 (no removal)."""
-    B, H, cap, D = k_cache.shape
-    G = freq.shape[1]
-    rc = load().ec_decode_score_step(_ptr(q, "q"), _ptr(k_new, "k_new"), _ptr(v_new, "v_new"), _ptr(k_cache, "k_cache"),
-                                     _ptr(v_cache, "v_cache"), _ptr(pos, "pos"), _ptr(freq, "freq"), B, H, G, D, cap,
-                                     cache_len, new_pos, scale, dtype_code(k_cache), _ptr(out, "out"), _ptr(ws, "ws"),
-                                     0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    if freq.dim() != 3:
+        raise ValueError("ec_decode_score_step: freq must be [B,G,cap]")
+    ptrs, po, (B, H, G, D, cap) = _decode_args(q, k_new, v_new, k_cache, v_cache, pos, out, freq.shape[1],
+                                               "ec_decode_score_step")
+    wp, wb = _ws(ws)
+    rc = _call(load().ec_decode_score_step, *ptrs, _chk(freq, "freq", torch.float32, (B, G, cap)), B, H, G, D, cap, cache_len,
+                                     new_pos, scale, dtype_code(k_cache), po, wp, wb, _stream)
     if check and rc != EC_OK:
         raise EcError("ec_decode_score_step", rc)
     return rc
@@ -235,32 +330,43 @@ def ec_decode_score_step(q, k_new, v_new, k_cache, v_cache, pos, freq, cache_len
 def ec_evict_min(k_cache, v_cache, pos, freq, length: int, protect_first: int, protect_recent: int, victim,
                  check=True) -> int:
     """Frequency policy: remove the least-mass row of every (b,g); victim [B,G] int32 receives the index."""
+    if k_cache.dim() != 4 or freq.dim() != 3:
+        raise ValueError("ec_evict_min: k_cache must be [B,H,cap,D] and freq [B,G,cap]")
     B, H, cap, D = k_cache.shape
-    G = freq.shape[1]
-    rc = load().ec_evict_min(_ptr(k_cache, "k_cache"), _ptr(v_cache, "v_cache"), _ptr(pos, "pos"), _ptr(freq, "freq"),
-                             B, H, G, D, cap, length, protect_first, protect_recent, dtype_code(k_cache),
-                             _ptr(victim, "victim"), _stream())
+    G = _groups(freq.shape[1], H, "ec_evict_min")
+    dt = k_cache.dtype
+    rc = _call(load().ec_evict_min, _chk(k_cache, "k_cache", dt, (B, H, cap, D)), _chk(v_cache, "v_cache", dt, (B, H, cap, D)),
+                             _chk(pos, "pos", torch.int32, (B, G, cap), True),
+                             _chk(freq, "freq", torch.float32, (B, G, cap)), B, H, G, D, cap, length, protect_first,
+                             protect_recent, dtype_code(k_cache), _chk(victim, "victim", torch.int32, (B, G)), _stream)
     if check and rc != EC_OK:
         raise EcError("ec_evict_min", rc)
     return rc
 
 
-def _i32(t, name, n):
+def _i32(t, name, n, optional=False):
     if t is None:
-        return None
+        if optional:
+            return None
+        raise ValueError(f"{name} is required")
     if t.dtype != torch.int32 or t.numel() != n:
         raise ValueError(f"{name} must be an int32 tensor of {n} entries")
-    return _ptr(t, name)
+    return _Checked(t, name)
 
 
 def ec_prefill_score_varlen(q, k, v, out, lse, score, seq_len, scale: float, ws, check=True) -> int:
     """Ragged batch: q,k,v [B,H,T_max,D], seq_len int32 [B] on the device."""
+    if q.dim() != 4 or score.dim() != 3:
+        raise ValueError("ec_prefill_score_varlen: q must be [B,H,T,D] and score [B,G,T]")
     B, H, T, D = q.shape
-    G = score.shape[1]
-    rc = load().ec_prefill_score_varlen(_ptr(q, "q"), _ptr(k, "k"), _ptr(v, "v"), _ptr(out, "out"), _ptr(lse, "lse"),
-                                        _ptr(score, "score"), _i32(seq_len, "seq_len", B), B, H, G, T, D, dtype_code(q),
-                                        scale, _ptr(ws, "ws"), 0 if ws is None else ws.numel() * ws.element_size(),
-                                        _stream())
+    G = _groups(score.shape[1], H, "ec_prefill_score_varlen")
+    dt, f32 = q.dtype, torch.float32
+    wp, wb = _ws(ws)
+    rc = _call(load().ec_prefill_score_varlen, _chk(q, "q", dt, (B, H, T, D)), _chk(k, "k", dt, (B, H, T, D)),
+                                        _chk(v, "v", dt, (B, H, T, D)), _chk(out, "out", dt, (B, H, T, D), True),
+                                        _chk(lse, "lse", f32, (B, H, T), True), _chk(score, "score", f32, (B, G, T)),
+                                        _i32(seq_len, "seq_len", B), B, H, G, T, D, dtype_code(q), scale, wp, wb,
+                                        _stream)
     if check and rc != EC_OK:
         raise EcError("ec_prefill_score_varlen", rc)
     return rc
@@ -269,10 +375,14 @@ def ec_prefill_score_varlen(q, k, v, out, lse, score, seq_len, scale: float, ws,
 def ec_select_anchors_varlen(score, seq_len, n_anchor_b, protect_first: int, protect_last: int, anchor_idx,
                              check=True) -> int:
     """Ragged batch: score [B,G,T_max], anchor_idx [B,G,n_max]; seq_len, n_anchor_b int32 [B] on the device."""
+    if score.dim() != 3 or anchor_idx.dim() != 3:
+        raise ValueError("ec_select_anchors_varlen: score and anchor_idx must be 3-D")
     B, G, T = score.shape
-    rc = load().ec_select_anchors_varlen(_ptr(score, "score"), _i32(seq_len, "seq_len", B),
-                                         _i32(n_anchor_b, "n_anchor_b", B), B, G, T, anchor_idx.shape[2], protect_first,
-                                         protect_last, _ptr(anchor_idx, "anchor_idx"), None, 0, _stream())
+    n_max = anchor_idx.shape[2]
+    rc = _call(load().ec_select_anchors_varlen, _chk(score, "score", torch.float32, (B, G, T)), _i32(seq_len, "seq_len", B),
+                                         _i32(n_anchor_b, "n_anchor_b", B), B, G, T, n_max, protect_first,
+                                         protect_last, _chk(anchor_idx, "anchor_idx", torch.int32, (B, G, n_max)),
+                                         None, 0, _stream)
     if check and rc != EC_OK:
         raise EcError("ec_select_anchors_varlen", rc)
     return rc
@@ -281,39 +391,45 @@ def ec_select_anchors_varlen(score, seq_len, n_anchor_b, protect_first: int, pro
 def ec_merge_compact_varlen(k, v, anchor_idx, seq_len, n_anchor_b, k_cache, v_cache, counts=None, assign=None, pos=None,
                             merge_mode: int = EC_MERGE_MEAN, check=True) -> int:
     """Ragged batch: k,v [B,H,T_max,D]; anchor_idx [B,G,n_max]; seq_len, n_anchor_b int32 [B] on the device."""
+    if k.dim() != 4 or anchor_idx.dim() != 3 or k_cache.dim() != 4:
+        raise ValueError("ec_merge_compact_varlen: k, k_cache must be 4-D and anchor_idx 3-D")
     B, H, T, D = k.shape
-    G, n_max = anchor_idx.shape[1], anchor_idx.shape[2]
-    rc = load().ec_merge_compact_varlen(_ptr(k, "k"), _ptr(v, "v"), _ptr(anchor_idx, "anchor_idx"),
+    G, n_max = _groups(anchor_idx.shape[1], H, "ec_merge_compact_varlen"), anchor_idx.shape[2]
+    cap = k_cache.shape[2]
+    dt, i32 = k.dtype, torch.int32
+    rc = _call(load().ec_merge_compact_varlen, _chk(k, "k", dt, (B, H, T, D)), _chk(v, "v", dt, (B, H, T, D)),
+                                        _chk(anchor_idx, "anchor_idx", i32, (B, G, n_max)),
                                         _i32(seq_len, "seq_len", B), _i32(n_anchor_b, "n_anchor_b", B), B, H, G, T, D,
-                                        n_max, dtype_code(k), merge_mode, _ptr(k_cache, "k_cache"),
-                                        _ptr(v_cache, "v_cache"), k_cache.shape[2], _ptr(counts, "counts"),
-                                        _ptr(assign, "assign"), _ptr(pos, "pos"), _stream())
+                                        n_max, dtype_code(k), merge_mode, _chk(k_cache, "k_cache", dt, (B, H, cap, D)),
+                                        _chk(v_cache, "v_cache", dt, (B, H, cap, D)), cap,
+                                        _chk(counts, "counts", i32, (B, G, n_max), True),
+                                        _chk(assign, "assign", i32, (B, G, T), True),
+                                        _chk(pos, "pos", i32, (B, G, cap), True), _stream)
     if check and rc != EC_OK:
         raise EcError("ec_merge_compact_varlen", rc)
     return rc
 
 
 def ec_decode_step_varlen(q, k_new, v_new, k_cache, v_cache, pos, cache_len_b, evict_idx_b, new_pos_b, scale: float,
-                          out, G: int | None = None, check=True) -> int:
+                          out, G: int | None = None, ws=None, check=True) -> int:
     """Ragged batch: per-sequence cache length, victim and position as int32 [B] device tensors."""
-    B, H, cap, D = k_cache.shape
-    if G is None:
-        G = pos.shape[1] if pos is not None else 1
-    rc = load().ec_decode_step_varlen(_ptr(q, "q"), _ptr(k_new, "k_new"), _ptr(v_new, "v_new"), _ptr(k_cache, "k_cache"),
-                                      _ptr(v_cache, "v_cache"), _ptr(pos, "pos"), _i32(cache_len_b, "cache_len_b", B),
-                                      _i32(evict_idx_b, "evict_idx_b", B), _i32(new_pos_b, "new_pos_b", B), B, H, G, D,
-                                      cap, scale, dtype_code(k_cache), _ptr(out, "out"), None, 0, _stream())
+    ptrs, po, (B, H, G, D, cap) = _decode_args(q, k_new, v_new, k_cache, v_cache, pos, out, G, "ec_decode_step_varlen")
+    wp, wb = _ws(ws)
+    rc = _call(load().ec_decode_step_varlen, *ptrs, _i32(cache_len_b, "cache_len_b", B),
+                                      _i32(evict_idx_b, "evict_idx_b", B, True), _i32(new_pos_b, "new_pos_b", B, True),
+                                      B, H, G, D, cap, scale, dtype_code(k_cache), po, wp, wb, _stream)
     if check and rc != EC_OK:
         raise EcError("ec_decode_step_varlen", rc)
     return rc
 
 
 def ec_importance_mean(score, T_new: int, P: int = 0, check=True) -> int:
-    """Table 3d's "Mean" metric, in place: score [B,G,P+T_new] f32 divided by the number of seeing queries."""
+    """A "Mean" metric (this library's reading of Table 3d's row), in place: score [B,G,P+T_new] f32 divided by
+    the number of queries that see each row."""
+    if score.dim() != 3:
+        raise ValueError("ec_importance_mean: score must be [B,G,P+T_new]")
     B, G, L = score.shape
-    if L != P + T_new or score.dtype != torch.float32:
-        raise ValueError("ec_importance_mean: score must be float32 [B,G,P+T_new]")
-    rc = load().ec_importance_mean(_ptr(score, "score"), B, G, T_new, P, _stream())
+    rc = _call(load().ec_importance_mean, _chk(score, "score", torch.float32, (B, G, P + T_new)), B, G, T_new, P, _stream)
     if check and rc != EC_OK:
         raise EcError("ec_importance_mean", rc)
     return rc
@@ -325,10 +441,10 @@ def ec_retention_step_varlen(n_seen_b, cache_len_b, evict_idx_b, new_pos_b, pend
                              check=True) -> int:
     """Device-side retention test of a ragged batch; all arrays int32 [B] on the device, updated in place."""
     B = n_seen_b.numel()
-    rc = load().ec_retention_step_varlen(_i32(n_seen_b, "n_seen_b", B), _i32(cache_len_b, "cache_len_b", B),
+    rc = _call(load().ec_retention_step_varlen, _i32(n_seen_b, "n_seen_b", B), _i32(cache_len_b, "cache_len_b", B),
                                          _i32(evict_idx_b, "evict_idx_b", B), _i32(new_pos_b, "new_pos_b", B),
                                          _i32(pending_b, "pending_b", B), B, gamma_num, gamma_den, budget_mode, fixed_len,
-                                         trunc_mode, recent, n_tl, protect_first, 1 if flush_only else 0, _stream())
+                                         trunc_mode, recent, n_tl, protect_first, 1 if flush_only else 0, _stream)
     if check and rc != EC_OK:
         raise EcError("ec_retention_step_varlen", rc)
     return rc

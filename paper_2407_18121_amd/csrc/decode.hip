@@ -3,10 +3,16 @@
 // the same launch (Sec. 3.1 Output Generation; Sec. 3.3; Alg. 1's last branch).
 //
 // HBM-bound: every K and V row of the cache is read exactly once with 16-byte
-// loads.  One workgroup of up to 16 waves owns a whole (batch, head), so nothing
-// is exchanged between workgroups (a split over workgroups was measured: the
-// device-scope release/acquire it needs costs far more than the extra
-// parallelism returns on this multi-die part).  A group of LPR = row_bytes/16
+// loads.  Two launch shapes:
+//   fused : one workgroup of up to 16 waves owns a whole (batch, head); nothing is exchanged
+//           between workgroups and the elimination is a register-held shift (below).
+//   split : when there are too few (batch, head) pairs to fill the chip, or too few bytes in flight
+//           per compute unit, the rows of one (batch, head) are divided over `splits` workgroups
+//           that each write an un-normalised partial (max, sum, weighted V) to the caller's
+//           workspace; a second, small launch merges the partials, writes the output and performs
+//           the append and the elimination through memory.  The two launches are ordered by the
+//           stream: no ticket, no device-scope fence inside a kernel.
+// A group of LPR = row_bytes/16
 // lanes owns one row per load, so a wave load covers 1 KB of contiguous cache;
 // each group keeps its own running (max, sum, weighted V) and never talks to
 // other groups inside the streaming loop.  Loads of the next tile are issued
@@ -15,6 +21,8 @@
 // after the workgroup barrier that ends all reads, the rows behind the evicted
 // one are stored one slot up straight from those registers, and so is the new
 // row -- the elimination costs no extra read.
+#include <algorithm>
+
 #include "ec_common.h"
 
 namespace ec {
@@ -256,6 +264,244 @@ __global__ __launch_bounds__(WAVES * kWave) void decode_step_kernel(
     }
 }
 
+// ------------------------------------------------------------------ split launch shape
+// Workgroup (bh, s) attends rows [s * chunk, (s + 1) * chunk) of its (batch, head), chunk =
+// ceil(n_rows / splits), and stores its partial to part[(bh * splits + s) * (D + 2)]: D weighted-V sums
+// relative to its own maximum, then that maximum (base-2 units; -inf for an empty range) and the sum of
+// its weights.  Nothing in the cache is written here.
+template <int DT, int D, int WAVES, int UNROLL>
+__global__ __launch_bounds__(WAVES * kWave) void decode_split_kernel(
+    const uint4* __restrict__ q, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
+    const uint4* __restrict__ k_cache, const uint4* __restrict__ v_cache, float* __restrict__ part, int H, int cap,
+    int cache_len, int splits, float scale_log2e, const int32_t* __restrict__ len_b)
+{
+    using S = DecodeShape<DT, D, WAVES, UNROLL>;
+    constexpr int LPR = S::kLPR, RPW = S::kRPW, EPL = S::kEPL, TILE = S::kTile;
+    const int bh = blockIdx.x / splits, sp = blockIdx.x % splits;
+    if (len_b) cache_len = min(max(len_b[bh / H], 0), cap - 1);
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int sub = lane % LPR, rgrp = lane / LPR;
+
+    const int n_rows = cache_len + 1;  // row cache_len is the new one, still in k_new/v_new
+    const int chunk = (n_rows + splits - 1) / splits;
+    const int r0 = sp * chunk, r1 = min(r0 + chunk, n_rows);
+    const int n_tiles = (max(r1 - r0, 0) + TILE - 1) / TILE;
+
+    const uint4* kc = k_cache + (size_t)bh * cap * LPR;
+    const uint4* vc = v_cache + (size_t)bh * cap * LPR;
+    const uint4* kn = k_new + (size_t)bh * LPR;
+    const uint4* vn = v_new + (size_t)bh * LPR;
+
+    float qf[EPL];
+    {
+        uint4 qc = q[(size_t)bh * LPR + sub];
+        unpack<DT>(qc, qf);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) qf[e] *= scale_log2e;
+    }
+    float m_run = -INFINITY, l_run = 0.f;
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+
+    uint4 kf[UNROLL], vf[UNROLL], kf2[UNROLL], vf2[UNROLL];
+    const int lane_row = wave * RPW + rgrp;
+    auto load_tile = [&](int t, uint4* kd, uint4* vd) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int r = r0 + t * TILE + u * (WAVES * RPW) + lane_row;
+            if (r < r1) {
+                const bool is_new = (r == cache_len);
+                kd[u] = load_stream(is_new ? kn + sub : kc + (size_t)r * LPR + sub);
+                vd[u] = load_stream(is_new ? vn + sub : vc + (size_t)r * LPR + sub);
+            } else {
+                kd[u] = make_uint4(0, 0, 0, 0);
+                vd[u] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    if (n_tiles > 0) load_tile(0, kf, vf);
+    for (int t = 0; t < n_tiles; ++t) {
+        const bool more = t + 1 < n_tiles;
+        if (more) load_tile(t + 1, kf2, vf2);
+        float s[UNROLL];
+        float m_tile = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int r = r0 + t * TILE + u * (WAVES * RPW) + lane_row;
+            float kx[EPL];
+            unpack<DT>(kf[u], kx);
+            float d = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) d = fmaf(qf[e], kx[e], d);
+            d = group_sum<LPR>(d);
+            s[u] = (r < r1) ? d : -INFINITY;
+            m_tile = fmaxf(m_tile, s[u]);
+        }
+        const float m_new = fmaxf(m_run, m_tile);
+        if (m_new > -INFINITY) {
+            const float corr = exp2f(m_run - m_new);
+            l_run *= corr;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] *= corr;
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const float p = exp2f(s[u] - m_new);
+                l_run += p;
+                float vx[EPL];
+                unpack<DT>(vf[u], vx);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vx[e], acc[e]);
+            }
+            m_run = m_new;
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            kf[u] = kf2[u];
+            vf[u] = vf2[u];
+        }
+    }
+    // row groups of a wave, then the waves: same order of operations as the fused kernel
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) {
+        const float m_o = __shfl_xor(m_run, off, kWave);
+        const float l_o = __shfl_xor(l_run, off, kWave);
+        const float m_n = fmaxf(m_run, m_o);
+        const float w_s = (m_run > -INFINITY) ? exp2f(m_run - m_n) : 0.f;
+        const float w_o = (m_o > -INFINITY) ? exp2f(m_o - m_n) : 0.f;
+        l_run = l_run * w_s + l_o * w_o;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+            const float a_o = __shfl_xor(acc[e], off, kWave);
+            acc[e] = acc[e] * w_s + a_o * w_o;
+        }
+        m_run = m_n;
+    }
+    __shared__ float sh_acc[WAVES][D];
+    __shared__ float sh_m[WAVES];
+    __shared__ float sh_l[WAVES];
+    if (rgrp == 0) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) sh_acc[wave][sub * EPL + e] = acc[e];
+        if (sub == 0) {
+            sh_m[wave] = m_run;
+            sh_l[wave] = l_run;
+        }
+    }
+    __syncthreads();
+    if (tid < D) {
+        float M = -INFINITY, L = 0.f, o_d = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) M = fmaxf(M, sh_m[w]);
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+            const float wt = (sh_m[w] > -INFINITY) ? exp2f(sh_m[w] - M) : 0.f;
+            L = fmaf(sh_l[w], wt, L);
+            o_d = fmaf(sh_acc[w][tid], wt, o_d);
+        }
+        float* dst = part + (size_t)blockIdx.x * (D + 2);
+        dst[tid] = o_d;
+        if (tid == 0) {
+            dst[D] = M;
+            dst[D + 1] = L;
+        }
+    }
+}
+
+// Second launch of the split shape, one workgroup per (batch, head): merges the partials in ascending split
+// order, writes the output, then appends the new row and removes the victim through memory (the rows behind
+// it move up by one, slab by slab: a slab is read completely before any of it is overwritten).
+constexpr int kCombineThreads = 256;
+template <int DT, int D>
+__global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(
+    const float* __restrict__ part, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new, uint4* k_cache,
+    uint4* v_cache, int32_t* pos, void* __restrict__ out, int H, int G, int cap, int cache_len, int evict_idx,
+    int32_t new_pos, int splits, const int32_t* __restrict__ len_b, const int32_t* __restrict__ evict_b,
+    const int32_t* __restrict__ new_pos_b)
+{
+    constexpr int LPR = D * Elem<DT>::kBytes / 16;
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    if (len_b) {
+        const int b = bh / H;
+        cache_len = min(max(len_b[b], 0), cap - 1);
+        evict_idx = evict_b ? min(max(evict_b[b], -1), cache_len) : -1;
+        if (new_pos_b) new_pos = new_pos_b[b];
+    }
+    if (tid < D) {
+        const float* p = part + (size_t)bh * splits * (D + 2);
+        float M = -INFINITY;
+        for (int s = 0; s < splits; ++s) M = fmaxf(M, p[s * (D + 2) + D]);
+        float L = 0.f, o_d = 0.f;
+        for (int s = 0; s < splits; ++s) {
+            const float ms = p[s * (D + 2) + D];
+            const float wt = (ms > -INFINITY) ? exp2f(ms - M) : 0.f;
+            L = fmaf(p[s * (D + 2) + D + 1], wt, L);
+            o_d = fmaf(p[s * (D + 2) + tid], wt, o_d);
+        }
+        const float r = o_d / L;
+        typename Elem<DT>::type* o = reinterpret_cast<typename Elem<DT>::type*>(out) + (size_t)bh * D;
+        if constexpr (DT == EC_F32)
+            o[tid] = r;
+        else
+            o[tid] = f32_to_bf16(r);
+    }
+
+    uint4* kc = k_cache + (size_t)bh * cap * LPR;
+    uint4* vc = v_cache + (size_t)bh * cap * LPR;
+    // rows evict_idx+1 .. cache_len-1 move up by one, then the new row lands behind them
+    const int n_move = (evict_idx >= 0) ? max(cache_len - 1 - evict_idx, 0) : 0;
+    const int total = n_move * LPR;
+    for (int c0 = 0; c0 < total; c0 += kCombineThreads) {
+        const int c = c0 + tid;
+        uint4 kk, vv;
+        if (c < total) {
+            kk = kc[(size_t)(evict_idx + 1) * LPR + c];
+            vv = vc[(size_t)(evict_idx + 1) * LPR + c];
+        }
+        __syncthreads();
+        if (c < total) {
+            kc[(size_t)evict_idx * LPR + c] = kk;
+            vc[(size_t)evict_idx * LPR + c] = vv;
+        }
+        __syncthreads();
+    }
+    const int new_row = (evict_idx < 0) ? cache_len : ((evict_idx == cache_len) ? -1 : cache_len - 1);
+    if (new_row >= 0 && tid < LPR) {
+        kc[(size_t)new_row * LPR + tid] = k_new[(size_t)bh * LPR + tid];
+        vc[(size_t)new_row * LPR + tid] = v_new[(size_t)bh * LPR + tid];
+    }
+    if (pos != nullptr && (G == H || (bh % H) == 0)) {
+        int32_t* pp = pos + ((size_t)(bh / H) * G + (G == 1 ? 0 : bh % H)) * cap;
+        for (int c0 = 0; c0 < n_move; c0 += kCombineThreads) {
+            const int c = c0 + tid;
+            int32_t pv = 0;
+            if (c < n_move) pv = pp[evict_idx + 1 + c];
+            __syncthreads();
+            if (c < n_move) pp[evict_idx + c] = pv;
+            __syncthreads();
+        }
+        if (new_row >= 0 && tid == 0) pp[new_row] = new_pos;
+    }
+}
+
+template <int DT, int D, int WAVES, int UNROLL>
+static int launch_decode_split(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                               int32_t* pos, int B, int H, int G, int cap, int cache_len, int evict_idx,
+                               int32_t new_pos, float scale, void* out, float* part, int splits, const int32_t* len_b,
+                               const int32_t* evict_b, const int32_t* new_pos_b, hipStream_t stream)
+{
+    using S = DecodeShape<DT, D, WAVES, UNROLL>;
+    hipLaunchKernelGGL((decode_split_kernel<DT, D, WAVES, UNROLL>), dim3(B * H * splits), dim3(S::kThreads), 0, stream,
+                       (const uint4*)q, (const uint4*)k_new, (const uint4*)v_new, (const uint4*)k_cache,
+                       (const uint4*)v_cache, part, H, cap, cache_len, splits, scale * kLog2e, len_b);
+    int rc = status_from_hip(hipGetLastError());
+    if (rc != EC_OK) return rc;
+    hipLaunchKernelGGL((decode_combine_kernel<DT, D>), dim3(B * H), dim3(kCombineThreads), 0, stream, part,
+                       (const uint4*)k_new, (const uint4*)v_new, (uint4*)k_cache, (uint4*)v_cache, pos, out, H, G, cap,
+                       cache_len, evict_idx, new_pos, splits, len_b, evict_b, new_pos_b);
+    return status_from_hip(hipGetLastError());
+}
+
 template <int DT, int D, int WAVES, int UNROLL>
 static int launch_decode_w(const void* q, const void* k_new, const void* v_new, void* k_cache,
                            void* v_cache, int32_t* pos, int B, int H, int G, int cap, int cache_len,
@@ -270,16 +516,58 @@ static int launch_decode_w(const void* q, const void* k_new, const void* v_new, 
     return status_from_hip(hipGetLastError());
 }
 
-// Workgroup width and loads in flight grow with the number of rows to stream.
+// Number of workgroups one (batch, head) is divided over.  The fused shape (1) is kept whenever the chip is
+// already covered twice over; otherwise rows are split so that about four workgroups' worth of loads are in
+// flight per compute unit, each split keeping at least 64 rows.
+int decode_auto_splits(int BH, int n_rows)
+{
+    constexpr int kCus = 256, kMaxSplits = 16;
+    if (BH >= 2 * kCus) return 1;
+    int s = (4 * kCus + BH - 1) / BH;
+    s = std::min(s, std::max(n_rows / 64, 1));
+    s = std::min(s, kMaxSplits);
+    return s < 2 ? 1 : s;
+}
+
+// Workspace floats the split shape needs at most (any cache length up to `cap` rows).
+size_t decode_part_floats(int B, int H, int cap, int D)
+{
+    const int s = decode_auto_splits(B * H, cap);
+    return s < 2 ? 0 : (size_t)B * H * s * (D + 2);
+}
+
+// Workgroup width and loads in flight grow with the number of rows to stream.  splits: 0 = choose, 1 = fused
+// kernel, n > 1 = n workgroups per (batch, head) + combine launch (needs `part`, part_floats >= B*H*n*(D+2)).
 template <int DT, int D>
 static int launch_decode(const void* q, const void* k_new, const void* v_new, void* k_cache,
                          void* v_cache, int32_t* pos, int B, int H, int G, int cap, int cache_len,
                          int evict_idx, int32_t new_pos, float scale, void* out, int forced_waves,
-                         int forced_unroll, const int32_t* len_b, const int32_t* evict_b, const int32_t* new_pos_b,
-                         hipStream_t stream)
+                         int forced_unroll, int splits, bool strict, float* part, size_t part_floats,
+                         const int32_t* len_b, const int32_t* evict_b, const int32_t* new_pos_b, hipStream_t stream)
 {
     const int n_rows = cache_len + 1;  // ragged batches pass the longest length the buffers allow
+    if (splits <= 0) splits = decode_auto_splits(B * H, n_rows);
+    if (splits > 1 && (part == nullptr || part_floats < (size_t)B * H * splits * (D + 2))) {
+        if (strict) return EC_EWORKSPACE;  // an explicit request that cannot be met
+        splits = 1;                        // no workspace: the fused shape needs none
+    }
     int waves = forced_waves, unroll = forced_unroll;
+    if (splits > 1) {
+        if (waves <= 0) waves = ((n_rows + splits - 1) / splits >= 192) ? 8 : 4;
+        if (unroll <= 0) unroll = 4;
+#define EC_DECODE_S(W_, U_)                                                                                    \
+    if (waves == W_ && unroll == U_)                                                                           \
+        return launch_decode_split<DT, D, W_, U_>(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, cap, cache_len, \
+                                                  evict_idx, new_pos, scale, out, part, splits, len_b, evict_b,    \
+                                                  new_pos_b, stream);
+        EC_DECODE_S(4, 4)
+        EC_DECODE_S(8, 4)
+        EC_DECODE_S(4, 8)
+        EC_DECODE_S(2, 4)
+        EC_DECODE_S(2, 8)
+#undef EC_DECODE_S
+        return EC_EINVAL;
+    }
     if (waves <= 0) waves = (n_rows >= 96) ? 8 : 4;  // measured: 8 waves x 4 loads each beats 16 x 4 at every shape
     if (unroll <= 0) unroll = 4;
 #define EC_DECODE_W(W_, U_)                                                                              \
@@ -297,16 +585,19 @@ static int launch_decode(const void* q, const void* k_new, const void* v_new, vo
     return EC_EINVAL;
 }
 
+// strict: the launch shape is an explicit request; a split without enough workspace is then an error instead
+// of falling back to the fused kernel.
 int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                     int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
                     int32_t new_pos, float scale, int dt, void* out, int forced_waves, int forced_unroll,
-                    const int32_t* len_b, const int32_t* evict_b, const int32_t* new_pos_b, hipStream_t stream)
+                    int splits, bool strict, float* part, size_t part_floats, const int32_t* len_b,
+                    const int32_t* evict_b, const int32_t* new_pos_b, hipStream_t stream)
 {
 #define EC_DECODE_CASE(DT_, D_)                                                                       \
     if (dt == DT_ && D == D_)                                                                         \
         return launch_decode<DT_, D_>(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, cap, cache_len,    \
-                                      evict_idx, new_pos, scale, out, forced_waves,       \
-                                      forced_unroll, len_b, evict_b, new_pos_b, stream);
+                                      evict_idx, new_pos, scale, out, forced_waves, forced_unroll, splits, \
+                                      strict, part, part_floats, len_b, evict_b, new_pos_b, stream);
     EC_DECODE_CASE(EC_BF16, 128)
     EC_DECODE_CASE(EC_BF16, 64)
     EC_DECODE_CASE(EC_F32, 128)

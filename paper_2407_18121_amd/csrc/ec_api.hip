@@ -1,6 +1,6 @@
 // C ABI of libelastic_cache: argument validation, workspace carving and dispatch.
 // No state, no allocation; every launch goes to the caller's stream.
-#include <cstdlib>
+#include <cmath>
 
 #include "ec_common.h"
 
@@ -8,7 +8,9 @@ namespace ec {
 int decode_dispatch(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                     int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
                     int32_t new_pos, float scale, int dt, void* out, int forced_waves, int forced_unroll,
-                    const int32_t* len_b, const int32_t* evict_b, const int32_t* new_pos_b, hipStream_t stream);
+                    int splits, bool strict, float* part, size_t part_floats, const int32_t* len_b,
+                    const int32_t* evict_b, const int32_t* new_pos_b, hipStream_t stream);
+size_t decode_part_floats(int B, int H, int cap, int D);
 int decode_score_dispatch(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                           int32_t* pos, float* freq, int B, int H, int G, int D, int cap, int cache_len,
                           int32_t new_pos, float scale, int dt, void* out, float* raw, float* stats,
@@ -42,12 +44,9 @@ bool shape_supported(int D, int dt) { return (D == 64 || D == 128) && (dt == EC_
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// Tuning/debug switches read from the environment on every call (host only).
-int env_int(const char* name, int dflt)
-{
-    const char* s = std::getenv(name);
-    return s ? std::atoi(s) : dflt;
-}
+// The softmax kernels take the row maximum before or after scaling depending on the path; a positive finite
+// scale makes the two orders agree (zero, negative, infinite and NaN scales are rejected).
+bool scale_ok(float scale) { return std::isfinite(scale) && scale > 0.f; }
 
 // Scoring pass of either entry point: Tq queries over L = P + Tq rows, heads of k/v kv_rows rows apart.
 int score_pass(const void* q, const void* k, const void* v, void* out, float* lse, float* score, int B, int H,
@@ -58,7 +57,7 @@ int score_pass(const void* q, const void* k, const void* v, void* out, float* ls
     if (B < 1 || H < 1 || geo.Tq < 1 || geo.P < 0 || D < 1) return EC_EINVAL;
     if (geo.kv_rows < geo.L) return EC_EINVAL;
     if (G != 1 && G != H) return EC_EINVAL;
-    if (!(scale == scale)) return EC_EINVAL;
+    if (!scale_ok(scale)) return EC_EINVAL;
     if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
     if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
     const size_t need = ec_workspace_bytes(EC_FN_PREFILL_SCORE, B, H, geo.L, D, dt);
@@ -74,10 +73,8 @@ int score_pass(const void* q, const void* k, const void* v, void* out, float* ls
     float* head_imp = (G == H) ? score : ws_imp;
 
     int rc;
-    const bool use_mfma = (dt == EC_BF16) && !env_int("EC_SCORE_FORCE_SIMT", 0);
-    if (use_mfma)
-        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, ws_vt, B, H, geo, seq_len, D, dt, scale,
-                                     env_int("EC_SCORE_WAVES", 0), s);
+    if (dt == EC_BF16)
+        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, ws_vt, B, H, geo, seq_len, D, dt, scale, 0, s);
     else
         rc = ec::score_simt_dispatch(q, k, v, out, lse_buf, head_imp, B, H, geo, seq_len, D, dt, scale, s);
     if (rc != EC_OK) return rc;
@@ -114,7 +111,9 @@ size_t ec_workspace_bytes(int fn, int B, int H, int T, int D, int dt)
         case EC_FN_MERGE_COMPACT: return 0;
         case EC_FN_DECODE_STEP:
             if (!shape_supported(D, dt)) return (size_t)-1;
-            return 0;  // one workgroup owns a whole (batch, head): nothing is staged in memory
+            // partial (max, sum, weighted V) of every split when one (batch, head) is divided over several
+            // workgroups; 0 when the batch alone fills the chip
+            return align256(ec::decode_part_floats(B, H, T, D) * sizeof(float));
         case EC_FN_DECODE_SCORE_STEP:
             if (!shape_supported(D, dt)) return (size_t)-1;
             // every row's scaled score [B,H,T] + softmax maximum and denominator [B,H,2], fp32
@@ -275,23 +274,43 @@ int ec_retention_step_varlen(int32_t* n_seen_b, int32_t* cache_len_b, int32_t* e
                                      reinterpret_cast<hipStream_t>(stream));
 }
 
-int ec_decode_step(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
-                   int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
-                   int32_t new_pos, float scale, int dt, void* out, void* ws, size_t ws_bytes, void* stream)
+namespace {
+int decode_step_checked(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                        int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
+                        int32_t new_pos, float scale, int dt, void* out, void* ws, size_t ws_bytes, int waves,
+                        int unroll, int splits, bool strict, void* stream)
 {
     if (!q || !k_new || !v_new || !k_cache || !v_cache || !out) return EC_EINVAL;
     if (B < 1 || H < 1 || D < 1 || cap < 1) return EC_EINVAL;
     if (G != 1 && G != H) return EC_EINVAL;
     if (cache_len < 0 || cache_len >= cap) return EC_EINVAL;
     if (evict_idx < -1 || evict_idx > cache_len) return EC_EINVAL;
-    if (!(scale == scale)) return EC_EINVAL;
+    if (!scale_ok(scale)) return EC_EINVAL;
+    if (waves < 0 || unroll < 0 || splits < 0 || splits > 64) return EC_EINVAL;
     if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
     if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
-    (void)ws;
-    (void)ws_bytes;
     return ec::decode_dispatch(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, D, cap, cache_len, evict_idx,
-                               new_pos, scale, dt, out, env_int("EC_DECODE_WAVES", 0), env_int("EC_DECODE_UNROLL", 0),
-                               nullptr, nullptr, nullptr, reinterpret_cast<hipStream_t>(stream));
+                               new_pos, scale, dt, out, waves, unroll, splits, strict, reinterpret_cast<float*>(ws),
+                               ws ? ws_bytes / sizeof(float) : 0, nullptr, nullptr, nullptr,
+                               reinterpret_cast<hipStream_t>(stream));
+}
+}  // namespace
+
+int ec_decode_step(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                   int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
+                   int32_t new_pos, float scale, int dt, void* out, void* ws, size_t ws_bytes, void* stream)
+{
+    return decode_step_checked(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, D, cap, cache_len, evict_idx, new_pos,
+                               scale, dt, out, ws, ws_bytes, 0, 0, 0, false, stream);
+}
+
+int ec_decode_step_shaped(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                          int32_t* pos, int B, int H, int G, int D, int cap, int cache_len, int evict_idx,
+                          int32_t new_pos, float scale, int dt, void* out, void* ws, size_t ws_bytes, int waves,
+                          int unroll, int splits, void* stream)
+{
+    return decode_step_checked(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, D, cap, cache_len, evict_idx, new_pos,
+                               scale, dt, out, ws, ws_bytes, waves, unroll, splits, true, stream);
 }
 
 int ec_decode_step_varlen(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
@@ -303,15 +322,13 @@ int ec_decode_step_varlen(const void* q, const void* k_new, const void* v_new, v
     if (B < 1 || H < 1 || D < 1 || cap < 1) return EC_EINVAL;
     if (G != 1 && G != H) return EC_EINVAL;
     if (pos && !new_pos_b) return EC_EINVAL;
-    if (!(scale == scale)) return EC_EINVAL;
+    if (!scale_ok(scale)) return EC_EINVAL;
     if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
     if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
-    (void)ws;
-    (void)ws_bytes;
     // the lengths live on the device: the launch shape is chosen for the longest cache the buffers allow
     return ec::decode_dispatch(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, D, cap, cap - 1, -1, 0, scale, dt, out,
-                               env_int("EC_DECODE_WAVES", 0), env_int("EC_DECODE_UNROLL", 0), cache_len_b, evict_idx_b,
-                               new_pos_b, reinterpret_cast<hipStream_t>(stream));
+                               0, 0, 0, false, reinterpret_cast<float*>(ws), ws ? ws_bytes / sizeof(float) : 0,
+                               cache_len_b, evict_idx_b, new_pos_b, reinterpret_cast<hipStream_t>(stream));
 }
 
 int ec_decode_score_step(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
@@ -322,7 +339,7 @@ int ec_decode_score_step(const void* q, const void* k_new, const void* v_new, vo
     if (B < 1 || H < 1 || D < 1 || cap < 1) return EC_EINVAL;
     if (G != 1 && G != H) return EC_EINVAL;
     if (cache_len < 0 || cache_len >= cap) return EC_EINVAL;
-    if (!(scale == scale)) return EC_EINVAL;
+    if (!scale_ok(scale)) return EC_EINVAL;
     if ((long long)B * H > 65535) return EC_EUNSUPPORTED;
     if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
     const size_t need = ec_workspace_bytes(EC_FN_DECODE_SCORE_STEP, B, H, cap, D, dt);

@@ -89,3 +89,80 @@ def test_evict_index_matches_oracle_everywhere():
         ec.ec_evict_index(0, 5, 1, 2)
     with pytest.raises(ec.EcError):
         ec.ec_evict_index(5, 5, 3, 2)
+
+
+def test_config_lengths_match_the_hand_worked_retention_table():
+    """The anchor count and cache capacity both sides of every parity test take from the config table are
+    Alg. 1's del_num rounding: pinned to tests/golden/retention_lengths.txt (worked in exact rationals)."""
+    from paper_2407_18121_amd import synthetic as syn
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "retention_lengths.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert {r[0] for r in rows} == set(syn.CONFIGS)
+    for name, T, p, q, steps, after_prompt, after_gen in rows:
+        cfg = syn.CONFIGS[name]
+        assert (cfg.T, cfg.gamma, cfg.decode_steps) == (int(T), (int(p), int(q)), int(steps)), name
+        assert cfg.n_anchor == int(after_prompt), name
+        assert cfg.cap == int(after_gen) + 1, name          # one spare row for the append before the removal
+        # and the library's own retention test walks from the first length to the second
+        n = cfg.n_anchor
+        for step in range(cfg.decode_steps):
+            n += 0 if ec.ec_evict_index(cfg.T + step + 1, n + 1, int(p), int(q)) >= 0 else 1
+            assert n < cfg.cap
+        assert n == int(after_gen), name
+
+
+def test_binding_rejects_wrong_types_and_shapes_before_any_call():
+    """The C ABI sees raw pointers only; the binding refuses tensors whose element type or shape does not fit
+    the call (a kernel would otherwise run out of bounds).  Host tensors: nothing is launched."""
+    import torch
+    B, H, T, D, G, cap, n = 2, 4, 16, 64, 1, 12, 8
+    f32, bf16, i32 = torch.float32, torch.bfloat16, torch.int32
+    q = torch.zeros((B, H, T, D), dtype=bf16)
+    score = torch.zeros((B, G, T), dtype=f32)
+    with pytest.raises(ValueError, match="score must be torch.float32"):
+        ec.ec_prefill_score(q, q, q, None, None, score.to(bf16), 0.1, None)
+    with pytest.raises(ValueError, match="lse must have shape"):
+        ec.ec_prefill_score(q, q, q, None, torch.zeros((B, H), dtype=f32), score, 0.1, None)
+    with pytest.raises(ValueError, match="k must be torch.bfloat16"):
+        ec.ec_prefill_score(q, q.float(), q, None, None, score, 0.1, None)
+    with pytest.raises(ValueError, match="v must have shape"):
+        ec.ec_prefill_score(q, q, q[:, :, :-1], None, None, score, 0.1, None)
+    with pytest.raises(ValueError, match="score groups"):
+        ec.ec_prefill_score(q, q, q, None, None, torch.zeros((B, 2, T), dtype=f32), 0.1, None)
+    with pytest.raises(ValueError, match="device memory"):   # everything fits: only the device is wrong
+        ec.ec_prefill_score(q, q, q, None, None, score, 0.1, None)
+    with pytest.raises(ValueError, match="anchor_idx must be torch.int32"):
+        ec.ec_select_anchors(score, n, 1, 1, torch.zeros((B, G, n), dtype=torch.int64))
+    with pytest.raises(ValueError, match="anchor_idx must have shape"):
+        ec.ec_select_anchors(score, n, 1, 1, torch.zeros((B, G, n - 1), dtype=i32))
+    kc = torch.zeros((B, H, cap, D), dtype=bf16)
+    a = torch.zeros((B, G, n), dtype=i32)
+    with pytest.raises(ValueError, match="v_cache must have shape"):
+        ec.ec_merge_compact(q, q, a, kc, kc[:, :, :-1], None, None, None)
+    with pytest.raises(ValueError, match="counts must have shape"):
+        ec.ec_merge_compact(q, q, a, kc, kc, torch.zeros((B, G, n + 1), dtype=i32), None, None)
+    with pytest.raises(ValueError, match="pos must be torch.int32"):
+        ec.ec_merge_compact(q, q, a, kc, kc, None, None, torch.zeros((B, G, cap), dtype=f32))
+    x = torch.zeros((B, H, D), dtype=bf16)
+    with pytest.raises(ValueError, match="k_new must have shape"):
+        ec.ec_decode_step(x, x[:, :1], x, kc, kc, None, 3, -1, 0, 0.1, x, None, G=1)
+    with pytest.raises(ValueError, match="out must be torch.bfloat16"):
+        ec.ec_decode_step(x, x, x, kc, kc, None, 3, -1, 0, 0.1, x.float(), None, G=1)
+    with pytest.raises(ValueError, match="q must be torch.bfloat16"):
+        ec.ec_decode_step(x.float(), x, x, kc, kc, None, 3, -1, 0, 0.1, x, None, G=1)
+    with pytest.raises(ValueError, match="freq must be torch.float32"):
+        ec.ec_decode_score_step(x, x, x, kc, kc, None, torch.zeros((B, G, cap), dtype=bf16), 3, 0, 0.1, x, None)
+    with pytest.raises(ValueError, match="victim must have shape"):
+        ec.ec_evict_min(kc, kc, None, torch.zeros((B, G, cap), dtype=f32), 5, 1, 1, torch.zeros((B,), dtype=i32))
+    with pytest.raises(ValueError, match="cache_len_b must be an int32 tensor"):
+        ec.ec_decode_step_varlen(x, x, x, kc, kc, None, torch.zeros((B + 1,), dtype=i32), None, None, 0.1, x, G=1)
+
+
+def test_scale_must_be_finite_and_positive():
+    lib = ec.load()
+    one = ctypes.c_void_p(256)
+    for bad in (0.0, -0.5, float("inf"), float("nan")):
+        assert lib.ec_prefill_score(one, one, one, None, None, one, 1, 1, 1, 8, 64, 0, bad, one, 1 << 20, None) == ec.EC_EINVAL
+        assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 64, 8, 3, -1, 0, bad, 0, one, None, 0, None) == ec.EC_EINVAL
+        assert lib.ec_decode_step_shaped(one, one, one, one, one, None, 1, 1, 1, 64, 8, 3, -1, 0, bad, 0, one, None, 0,
+                                         0, 0, 0, None) == ec.EC_EINVAL

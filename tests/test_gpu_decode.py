@@ -11,7 +11,9 @@ from util import assert_close, quantize, to_dev, to_host, torch_dtype
 pytestmark = pytest.mark.gpu
 
 
-def _case(dtype, D, B, H, G, cap, cache_len, evict_idx, seed, scale=None):
+def _case(dtype, D, B, H, G, cap, cache_len, evict_idx, seed, scale=None, shape=None):
+    """One call against the oracle.  shape = (waves, unroll, splits) goes through ec_decode_step_shaped with a
+    workspace sized for that many splits; None = ec_decode_step with the workspace it asks for."""
     rng = np.random.default_rng(seed)
     scale = (1.0 / np.sqrt(D)) if scale is None else scale
     kc = np.zeros((B, H, cap, D), np.float32)
@@ -34,9 +36,15 @@ def _case(dtype, D, B, H, G, cap, cache_len, evict_idx, seed, scale=None):
     dkc, dvc = to_dev(kc, dtype), to_dev(vc, dtype)
     dpos = torch.from_numpy(pos).cuda()
     dout = torch.full((B, H, D), float("nan"), dtype=torch_dtype(dtype), device="cuda")
-    ws = ec.new_workspace(ec.EC_FN_DECODE_STEP, B, H, cap, D, ec.dtype_code(dkc))
-    ec.ec_decode_step(to_dev(q, dtype), to_dev(kn, dtype), to_dev(vn, dtype), dkc, dvc, dpos, cache_len,
-                      evict_idx, 4242, scale, dout, ws)
+    if shape is None:
+        ws = ec.new_workspace(ec.EC_FN_DECODE_STEP, B, H, cap, D, ec.dtype_code(dkc))
+        ec.ec_decode_step(to_dev(q, dtype), to_dev(kn, dtype), to_dev(vn, dtype), dkc, dvc, dpos, cache_len,
+                          evict_idx, 4242, scale, dout, ws)
+    else:
+        waves, unroll, splits = shape
+        ws = torch.full((4 * B * H * max(splits, 1) * (D + 2) + 256,), 0xFF, dtype=torch.uint8, device="cuda")
+        ec.ec_decode_step_shaped(to_dev(q, dtype), to_dev(kn, dtype), to_dev(vn, dtype), dkc, dvc, dpos, cache_len,
+                                 evict_idx, 4242, scale, dout, ws, waves=waves, unroll=unroll, splits=splits)
     torch.cuda.synchronize()
     assert_close(to_host(dout), oout, dtype, "out")
     n_after = cache_len + (0 if evict_idx >= 0 else 1)
@@ -63,12 +71,56 @@ def test_decode_step_shapes(dtype, D, B, H, G, cap, cache_len, evict_idx):
 
 
 @pytest.mark.parametrize("waves", [4, 8, 16])
-def test_decode_step_workgroup_widths(waves, monkeypatch):
-    monkeypatch.setenv("EC_DECODE_WAVES", str(waves))
-    _case("bf16", 128, 2, 3, 1, 900, 777, 777 - 25, seed=waves)
-    _case("f32", 64, 1, 4, 4, 900, 130, 3, seed=waves + 100)     # more than one tile moves
-    _case("bf16", 64, 1, 2, 2, 900, 511, 511, seed=waves + 200)  # victim = new row, full tiles
-    _case("f32", 128, 1, 2, 1, 900, 512, 1, seed=waves + 300)
+def test_decode_step_workgroup_widths(waves):
+    shape = (waves, 0, 1)   # one workgroup per (batch, head), explicit width
+    _case("bf16", 128, 2, 3, 1, 900, 777, 777 - 25, seed=waves, shape=shape)
+    _case("f32", 64, 1, 4, 4, 900, 130, 3, seed=waves + 100, shape=shape)     # more than one tile moves
+    _case("bf16", 64, 1, 2, 2, 900, 511, 511, seed=waves + 200, shape=shape)  # victim = new row, full tiles
+    _case("f32", 128, 1, 2, 1, 900, 512, 1, seed=waves + 300, shape=shape)
+
+
+@pytest.mark.parametrize("splits", [2, 3, 8, 16])
+@pytest.mark.parametrize("waves,unroll", [(4, 4), (8, 4), (2, 8)])
+def test_decode_step_split_over_workgroups(splits, waves, unroll):
+    """The rows of one (batch, head) divided over several workgroups + the merging launch: same outputs, and
+    the append / elimination through memory moves rows bit for bit, wherever the victim lies."""
+    shape = (waves, unroll, splits)
+    _case("bf16", 128, 2, 3, 1, 900, 777, 777 - 25, seed=splits, shape=shape)
+    _case("bf16", 128, 1, 2, 2, 900, 640, -1, seed=splits + 50, shape=shape)      # append only
+    _case("f32", 64, 1, 4, 4, 900, 130, 3, seed=splits + 100, shape=shape)        # victim in the first split
+    _case("bf16", 64, 1, 2, 2, 900, 511, 511, seed=splits + 200, shape=shape)     # victim = new row
+    _case("f32", 128, 1, 2, 1, 900, 512, 0, seed=splits + 300, shape=shape)       # whole cache moves
+    _case("bf16", 128, 1, 2, 1, 40, 5, 2, seed=splits + 400, shape=shape)         # more splits than rows
+    _case("bf16", 128, 1, 2, 1, 40, 0, -1, seed=splits + 500, shape=shape)        # empty cache: out = v_new
+
+
+def test_decode_split_length_and_victim_sweep():
+    """Split shape over cache lengths around its tile and chunk sizes, every kind of victim."""
+    for n in [0, 1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 191, 192, 193, 255, 256, 257, 511, 512, 513]:
+        for vic in sorted({-1, 0, n // 2, max(n - 25, 0), n}):
+            _case("bf16", 128, B=1, H=2, G=1, cap=n + 2, cache_len=n, evict_idx=vic, seed=9000 + n * 10 + vic,
+                  shape=(0, 0, 4))
+
+
+def test_decode_step_library_choice_with_workspace():
+    """ec_decode_step with the workspace it asks for takes the split shape when B*H is small: checked at a
+    small-batch shape, and the same call without a workspace takes the single-workgroup shape."""
+    B, H, D, cap = 1, 8, 128, 700
+    assert ec.ec_workspace_bytes(ec.EC_FN_DECODE_STEP, B, H, cap, D, ec.EC_BF16) > 0
+    assert ec.ec_workspace_bytes(ec.EC_FN_DECODE_STEP, 16, 32, cap, D, ec.EC_BF16) == 0
+    _case("bf16", D, B, H, 1, cap, 640, 640 - 25, seed=31)
+    _case("bf16", D, B, H, H, cap, 640, -1, seed=32)
+
+
+def test_shaped_call_rejects_what_it_cannot_launch():
+    B, H, D, cap = 1, 2, 128, 64
+    z = lambda *s: torch.zeros(s, dtype=torch.bfloat16, device="cuda")
+    small = torch.zeros(256, dtype=torch.uint8, device="cuda")
+    args = (z(B, H, D), z(B, H, D), z(B, H, D), z(B, H, cap, D), z(B, H, cap, D), None, 10, -1, 0, 0.1, z(B, H, D))
+    assert ec.ec_decode_step_shaped(*args, small, splits=8, G=1, check=False) == ec.EC_EWORKSPACE
+    assert ec.ec_decode_step_shaped(*args, small, waves=5, splits=1, G=1, check=False) == ec.EC_EINVAL
+    assert ec.ec_decode_step_shaped(*args, None, splits=1, G=1, check=False) == ec.EC_OK
+    torch.cuda.synchronize()
 
 
 def test_back_to_back_calls_of_different_lengths():

@@ -5,6 +5,8 @@ bits.  Where the fp64 brute force of a whole layer would take minutes, the oracl
 batch elements (all heads of each, so the layer-wise head mean is complete) and the rest of the
 output is checked through properties that hold at any size.
 """
+import functools
+
 import numpy as np
 import pytest
 import torch
@@ -115,37 +117,65 @@ def test_prefill_chain_full_shape(name):
         assert (lhs - rhs).abs().max().item() <= 2.0 ** -8 * float((v[b].float().abs()).sum(1).max()) + 1e-2
 
 
+@functools.lru_cache(maxsize=None)
+def _oracle_merged_cache(name, b):
+    """The oracle's own compressed cache of batch element b of the workload's prompt (layer 3): scores, anchors,
+    buckets and bucket means, all in fp64 from host copies of the prompt bits.  Returns (anchors, K rows, V rows)."""
+    cfg = syn.CONFIGS[name]
+    q, k, v = synt.prompt_qkv_device(cfg, layer=3)
+    qb, kb, vb = (_host(x[b:b + 1]) for x in (q, k, v))
+    del q, k, v
+    ref = oracle.prefill_score(qb, kb, vb, cfg.scale, 1, want_out=False)
+    a = oracle.select_anchors(ref["score"].astype(np.float32), cfg.n_anchor, 1, 1)
+    assign, _ = oracle.assign_nearest(a, cfg.T)
+    return a, oracle.merge_compact(kb, assign, cfg.n_anchor), oracle.merge_compact(vb, assign, cfg.n_anchor)
+
+
 @pytest.mark.parametrize("name", ALL)
 def test_decode_full_shape(name):
+    """Every generated token of the workload (Alg. 1's last branch over the whole schedule) on one layer, in the
+    launch configuration the benchmark times (workspace given: the library picks its launch shape).  The sampled
+    batch elements start from the ORACLE's compressed prompt cache, rounded to the storage type on both sides,
+    and are compared with the oracle at every step; the other batch elements start from random rows."""
     cfg = syn.CONFIGS[name]
-    B, H, D, cap = cfg.B, cfg.H, cfg.D, cfg.cap
+    B, H, D, cap, nA = cfg.B, cfg.H, cfg.D, cfg.cap, cfg.n_anchor
     dt = synt.torch_dtype(cfg)
     g = torch.Generator(device="cuda").manual_seed(1234 + cfg.cid)
     kc = (torch.randn((B, H, cap, D), generator=g, device="cuda") * 1.5).to(dt)
     vc = torch.randn((B, H, cap, D), generator=g, device="cuda").to(dt)
     kc[:, :, 0] *= 8
     pos = (torch.arange(cap, device="cuda", dtype=torch.int32) * 2).repeat(B, 1, 1).contiguous()
+    samples = SAMPLES[name]
+    for b in samples:
+        a, mk, mv = _oracle_merged_cache(name, b)
+        kc[b, :, :nA] = torch.from_numpy(mk[0]).to(device="cuda", dtype=dt)
+        vc[b, :, :nA] = torch.from_numpy(mv[0]).to(device="cuda", dtype=dt)
+        pos[b, 0, :nA] = torch.from_numpy(a[0, 0]).cuda()
     dq, dk, dv = synt.decode_stream_device(cfg, layer=1)
     out = torch.empty((B, H, D), dtype=dt, device="cuda")
+    ws = ec.new_workspace(ec.EC_FN_DECODE_STEP, B, H, cap, D, ec.dtype_code(kc))
     p, qd = cfg.gamma
-    samples = SAMPLES[name]
-    okc, ovc = (to_host(x[samples]).copy() for x in (kc, vc))
+    okc, ovc = (to_host(x[samples]).copy() for x in (kc, vc))   # the same bits, widened exactly
     opos = pos[samples].cpu().numpy().copy()
-    N = cfg.n_anchor
-    n_steps = 40                      # crosses appends and evictions at the ratio budget
-    for step in range(n_steps):
+    hq, hk, hv = (_host(x[:, samples]) for x in (dq, dk, dv))
+    N = nA
+    worst = 0.0
+    for step in range(cfg.decode_steps):
         n_seen = cfg.T + step + 1
         idx = ec.ec_evict_index(n_seen, N + 1, p, qd)
-        ec.ec_decode_step(dq[step], dk[step], dv[step], kc, vc, pos, N, idx, n_seen - 1, cfg.scale, out, None)
-        o_ref, _ = oracle.decode_step(_host(dq[step][samples]), _host(dk[step][samples]), _host(dv[step][samples]),
-                                      okc, ovc, opos, N, idx, n_seen - 1, cfg.scale)
-        assert_close(to_host(out[samples]), o_ref, cfg.dtype, f"out step {step}")
+        ec.ec_decode_step(dq[step], dk[step], dv[step], kc, vc, pos, N, idx, n_seen - 1, cfg.scale, out, ws)
+        o_ref, _ = oracle.decode_step(hq[step], hk[step], hv[step], okc, ovc, opos, N, idx, n_seen - 1, cfg.scale)
+        got = to_host(out[samples])
+        worst = max(worst, float(np.abs(got - o_ref).max()))
+        assert_close(got, o_ref, cfg.dtype, f"out step {step}")
         N += 0 if idx >= 0 else 1
+        assert N == -((-p * n_seen) // qd)                       # ceil(gamma * tokens seen) after every step
     torch.cuda.synchronize()
+    assert N == -((-p * (cfg.T + cfg.decode_steps)) // qd) == cap - 1
     np.testing.assert_array_equal(to_host(kc[samples])[:, :, :N], okc[:, :, :N])
     np.testing.assert_array_equal(to_host(vc[samples])[:, :, :N], ovc[:, :, :N])
     np.testing.assert_array_equal(pos[samples].cpu().numpy()[:, :, :N], opos[:, :, :N])
-    # every other batch element: finite outputs, positions strictly increasing, untouched tail
+    # every other batch element: finite outputs, positions strictly increasing
     assert torch.isfinite(out.float()).all()
     assert (pos[:, :, 1:N] > pos[:, :, :N - 1]).all()
 
