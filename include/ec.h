@@ -10,7 +10,8 @@
  *  - Pointers named below as DEVICE point to memory of the current HIP device,
  *    owned by the caller for the whole call and until the stream has drained.
  *    The library allocates nothing and frees nothing; scratch comes from the
- *    caller's workspace `ws` (size from ec_workspace_bytes).
+ *    caller's workspace `ws` (size from ec_workspace_bytes), except in
+ *    ec_decode_score_step_static, which uses an array built into the library.
  *  - All tensors are dense, row-major, in the element type `dt` unless a C type
  *    is given.  Prompt tensors are [B,H,T,D] (sequence on axis 2, as Alg. 1
  *    reads it), caches are [B,H,cap,D].  Positions are 0-based.
@@ -338,6 +339,21 @@ int ec_decode_score_step(const void* q, const void* k_new, const void* v_new, vo
                          void* v_cache, int32_t* pos, float* freq, int B, int H, int G, int D, int cap,
                          int cache_len, int32_t new_pos, float scale, int dt, void* out, void* ws,
                          size_t ws_bytes, void* stream);
+
+/*
+ * ec_decode_score_step for callers that cannot provide device scratch of their own and must not allocate:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus
+ * the workspace; the scratch (every row's score and the softmax statistics, 4*B*H*(cap+2) bytes rounded up
+ * to 256-byte blocks) lives in an array built into the library, 4 MiB per GPU the library runs on, held
+ * until the process ends.  Shapes that need more return EC_EWORKSPACE and launch nothing.  The call
+ * allocates and frees nothing.  The array's device address is looked up on the first call on each device
+ * (make that call outside a stream capture).  All calls on one GPU share the array: calls that overlap in
+ * time on one GPU (different streams, or threads) race; calls on one stream are ordered and safe.  Nothing
+ * in the array needs to start at zero: every word read is written earlier in the same call.
+ */
+int ec_decode_score_step_static(const void* q, const void* k_new, const void* v_new, void* k_cache,
+                                void* v_cache, int32_t* pos, float* freq, int B, int H, int G, int D, int cap,
+                                int cache_len, int32_t new_pos, float scale, int dt, void* out, void* stream);
 
 /*
  * ec_evict_min removes, for every (b,g), the row of least mass among rows protect_first ..

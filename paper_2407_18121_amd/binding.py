@@ -25,7 +25,8 @@ EC_MERGE_MEAN, EC_MERGE_EVICT = 0, 1
 SYMBOLS = ("ec_status_string", "ec_workspace_bytes", "ec_prefill_score", "ec_chunk_score", "ec_select_anchors",
            "ec_merge_compact", "ec_remerge_compact", "ec_evict_index", "ec_decode_step", "ec_decode_score_step",
            "ec_evict_min", "ec_prefill_score_varlen", "ec_select_anchors_varlen", "ec_merge_compact_varlen",
-           "ec_decode_step_varlen", "ec_importance_mean", "ec_retention_step_varlen", "ec_decode_step_shaped")
+           "ec_decode_step_varlen", "ec_importance_mean", "ec_retention_step_varlen", "ec_decode_step_shaped",
+           "ec_decode_score_step_static")
 
 _lib = None
 
@@ -70,6 +71,8 @@ def load():
     lib.ec_decode_step_shaped.restype = c_int
     lib.ec_decode_score_step.argtypes = ([c_vp] * 7 + [c_int] * 6 + [ctypes.c_int32, c_f, c_int, c_vp, c_vp, c_sz, c_vp])
     lib.ec_decode_score_step.restype = c_int
+    lib.ec_decode_score_step_static.argtypes = ([c_vp] * 7 + [c_int] * 6 + [ctypes.c_int32, c_f, c_int, c_vp, c_vp])
+    lib.ec_decode_score_step_static.restype = c_int
     lib.ec_evict_min.argtypes = [c_vp] * 4 + [c_int] * 9 + [c_vp, c_vp]
     lib.ec_evict_min.restype = c_int
     lib.ec_prefill_score_varlen.argtypes = [c_vp] * 7 + [c_int] * 6 + [c_f, c_vp, c_sz, c_vp]
@@ -324,6 +327,20 @@ def ec_decode_score_step(q, k_new, v_new, k_cache, v_cache, pos, freq, cache_len
                                      new_pos, scale, dtype_code(k_cache), po, wp, wb, _stream)
     if check and rc != EC_OK:
         raise EcError("ec_decode_score_step", rc)
+    return rc
+
+
+def ec_decode_score_step_static(q, k_new, v_new, k_cache, v_cache, pos, freq, cache_len: int, new_pos: int,
+                                scale: float, out, check=True) -> int:
+    """ec_decode_score_step on the library's built-in scratch: no workspace argument, nothing allocated."""
+    if freq.dim() != 3:
+        raise ValueError("ec_decode_score_step_static: freq must be [B,G,cap]")
+    ptrs, po, (B, H, G, D, cap) = _decode_args(q, k_new, v_new, k_cache, v_cache, pos, out, freq.shape[1],
+                                               "ec_decode_score_step_static")
+    rc = _call(load().ec_decode_score_step_static, *ptrs, _chk(freq, "freq", torch.float32, (B, G, cap)), B, H, G, D,
+               cap, cache_len, new_pos, scale, dtype_code(k_cache), po, _stream)
+    if check and rc != EC_OK:
+        raise EcError("ec_decode_score_step_static", rc)
     return rc
 
 

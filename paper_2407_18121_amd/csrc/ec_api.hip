@@ -1,6 +1,8 @@
 // C ABI of libelastic_cache: argument validation, workspace carving and dispatch.
-// No state, no allocation; every launch goes to the caller's stream.
+// No allocation; every launch goes to the caller's stream.  The only state is the per-device address of
+// the built-in scratch array of ec_decode_score_step_static, looked up once.
 #include <cmath>
+#include <mutex>
 
 #include "ec_common.h"
 
@@ -38,7 +40,30 @@ int importance_mean_launch(float* score, int B, int G, int Tq, int P, hipStream_
 int head_mean_launch(const float* head_imp, float* score, int B, int H, int T, hipStream_t stream);
 }  // namespace ec
 
+// Scratch of ec_decode_score_step_static: one array per GPU the library runs on, held until the process
+// ends.  The name below is only a host-side handle; the device address is looked up once per device.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device), or nullptr.
+void* static_scratch_ptr()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
 
 bool shape_supported(int D, int dt) { return (D == 64 || D == 128) && (dt == EC_F32 || dt == EC_BF16); }
 
@@ -348,6 +373,22 @@ int ec_decode_score_step(const void* q, const void* k_new, const void* v_new, vo
     float* stats = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align256((size_t)B * H * cap * sizeof(float)));
     return ec::decode_score_dispatch(q, k_new, v_new, k_cache, v_cache, pos, freq, B, H, G, D, cap, cache_len, new_pos,
                                      scale, dt, out, raw, stats, reinterpret_cast<hipStream_t>(stream));
+}
+
+int ec_decode_score_step_static(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                                int32_t* pos, float* freq, int B, int H, int G, int D, int cap, int cache_len,
+                                int32_t new_pos, float scale, int dt, void* out, void* stream)
+{
+    if (B < 1 || H < 1 || cap < 1) return EC_EINVAL;
+    if (!shape_supported(D, dt)) return EC_EUNSUPPORTED;
+    const size_t need = ec_workspace_bytes(EC_FN_DECODE_SCORE_STEP, B, H, cap, D, dt);
+    if (need == (size_t)-1 || need > kStaticScratchBytes) return EC_EWORKSPACE;  // beyond the built-in scratch
+    void* ptr = static_scratch_ptr();
+    if (!ptr) return EC_EDEVICE;
+    // every word of the scratch the second kernel reads is written by the first one in the same call:
+    // nothing has to start at zero
+    return ec_decode_score_step(q, k_new, v_new, k_cache, v_cache, pos, freq, B, H, G, D, cap, cache_len, new_pos,
+                                scale, dt, out, ptr, kStaticScratchBytes, stream);
 }
 
 int ec_evict_min(void* k_cache, void* v_cache, int32_t* pos, float* freq, int B, int H, int G, int D, int cap,
