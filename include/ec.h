@@ -239,12 +239,12 @@ int ec_evict_index(int64_t n_seen, int len_after_append, int gamma_num, int gamm
  *   pos               DEVICE [B,G,cap] int32 original position of every row, updated
  *                     like the cache; may be NULL
  *   out               DEVICE [B,H,D] dt, written
- *   ws                DEVICE scratch, optional.  With ec_workspace_bytes(EC_FN_DECODE_STEP, B,H,cap,D,dt)
- *                     bytes (0 when B*H alone fills the chip) the rows of one (batch, head) may be
- *                     divided over several workgroups whose partial results meet in ws and are
- *                     merged by a second launch on the same stream; with ws NULL or smaller, one
- *                     workgroup streams a whole (batch, head) and nothing is staged.  Both shapes
- *                     compute the same function; cache moves are bit-exact in both.
+ *   ws                DEVICE scratch, optional: ec_workspace_bytes(EC_FN_DECODE_STEP, B,H,cap,D,dt)
+ *                     bytes, which is 0 for the launch shape the library picks itself (one workgroup
+ *                     streams a whole (batch, head); nothing is staged), so ws may be NULL.  A shape
+ *                     that divides a (batch, head) over several workgroups, whose partial results
+ *                     meet in ws and are merged by a second launch on the same stream, exists and is
+ *                     reached through ec_decode_step_shaped; it measured slower at every workload.
  * Requires 0 <= cache_len < cap, -1 <= evict_idx <= cache_len and a finite scale > 0.  Dot
  * products and the softmax are evaluated in fp32.
  */

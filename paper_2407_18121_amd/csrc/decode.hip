@@ -272,13 +272,12 @@ __global__ __launch_bounds__(WAVES * kWave) void decode_step_kernel(
 template <int DT, int D, int WAVES, int UNROLL>
 __global__ __launch_bounds__(WAVES * kWave) void decode_split_kernel(
     const uint4* __restrict__ q, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new,
-    const uint4* __restrict__ k_cache, const uint4* __restrict__ v_cache, float* __restrict__ part, int H, int cap,
-    int cache_len, int splits, float scale_log2e, const int32_t* __restrict__ len_b)
+    const uint4* __restrict__ k_cache, const uint4* __restrict__ v_cache, float* __restrict__ part, int cap,
+    int cache_len, int splits, float scale_log2e)
 {
     using S = DecodeShape<DT, D, WAVES, UNROLL>;
     constexpr int LPR = S::kLPR, RPW = S::kRPW, EPL = S::kEPL, TILE = S::kTile;
     const int bh = blockIdx.x / splits, sp = blockIdx.x % splits;
-    if (len_b) cache_len = min(max(len_b[bh / H], 0), cap - 1);
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int sub = lane % LPR, rgrp = lane / LPR;
 
@@ -416,17 +415,10 @@ template <int DT, int D>
 __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(
     const float* __restrict__ part, const uint4* __restrict__ k_new, const uint4* __restrict__ v_new, uint4* k_cache,
     uint4* v_cache, int32_t* pos, void* __restrict__ out, int H, int G, int cap, int cache_len, int evict_idx,
-    int32_t new_pos, int splits, const int32_t* __restrict__ len_b, const int32_t* __restrict__ evict_b,
-    const int32_t* __restrict__ new_pos_b)
+    int32_t new_pos, int splits)
 {
     constexpr int LPR = D * Elem<DT>::kBytes / 16;
     const int bh = blockIdx.x, tid = threadIdx.x;
-    if (len_b) {
-        const int b = bh / H;
-        cache_len = min(max(len_b[b], 0), cap - 1);
-        evict_idx = evict_b ? min(max(evict_b[b], -1), cache_len) : -1;
-        if (new_pos_b) new_pos = new_pos_b[b];
-    }
     if (tid < D) {
         const float* p = part + (size_t)bh * splits * (D + 2);
         float M = -INFINITY;
@@ -487,18 +479,17 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(
 template <int DT, int D, int WAVES, int UNROLL>
 static int launch_decode_split(const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                                int32_t* pos, int B, int H, int G, int cap, int cache_len, int evict_idx,
-                               int32_t new_pos, float scale, void* out, float* part, int splits, const int32_t* len_b,
-                               const int32_t* evict_b, const int32_t* new_pos_b, hipStream_t stream)
+                               int32_t new_pos, float scale, void* out, float* part, int splits, hipStream_t stream)
 {
     using S = DecodeShape<DT, D, WAVES, UNROLL>;
     hipLaunchKernelGGL((decode_split_kernel<DT, D, WAVES, UNROLL>), dim3(B * H * splits), dim3(S::kThreads), 0, stream,
                        (const uint4*)q, (const uint4*)k_new, (const uint4*)v_new, (const uint4*)k_cache,
-                       (const uint4*)v_cache, part, H, cap, cache_len, splits, scale * kLog2e, len_b);
+                       (const uint4*)v_cache, part, cap, cache_len, splits, scale * kLog2e);
     int rc = status_from_hip(hipGetLastError());
     if (rc != EC_OK) return rc;
     hipLaunchKernelGGL((decode_combine_kernel<DT, D>), dim3(B * H), dim3(kCombineThreads), 0, stream, part,
                        (const uint4*)k_new, (const uint4*)v_new, (uint4*)k_cache, (uint4*)v_cache, pos, out, H, G, cap,
-                       cache_len, evict_idx, new_pos, splits, len_b, evict_b, new_pos_b);
+                       cache_len, evict_idx, new_pos, splits);
     return status_from_hip(hipGetLastError());
 }
 
@@ -516,17 +507,17 @@ static int launch_decode_w(const void* q, const void* k_new, const void* v_new, 
     return status_from_hip(hipGetLastError());
 }
 
-// Number of workgroups one (batch, head) is divided over.  The fused shape (1) is kept whenever the chip is
-// already covered twice over; otherwise rows are split so that about four workgroups' worth of loads are in
-// flight per compute unit, each split keeping at least 64 rows.
+// Number of workgroups one (batch, head) is divided over when the caller leaves the choice to the library.
+// Measured on MI355X (graph replay, 32 layers): the merging launch costs about as much as an empty dispatch
+// (3-5 us), which is more than the split saves at every workload shape tried -- B*H = 32, 640 rows: 9.9 us
+// fused, 10.3 us best split; B*H = 160: 13.1 vs 16.8 us; B*H = 256: 16.0 vs 20.2 us -- because one launch is
+// ~3 us of dispatch plus bytes at 5.3-5.9 TB/s already.  The library therefore always picks the fused shape;
+// the split shape stays reachable through ec_decode_step_shaped.
 int decode_auto_splits(int BH, int n_rows)
 {
-    constexpr int kCus = 256, kMaxSplits = 16;
-    if (BH >= 2 * kCus) return 1;
-    int s = (4 * kCus + BH - 1) / BH;
-    s = std::min(s, std::max(n_rows / 64, 1));
-    s = std::min(s, kMaxSplits);
-    return s < 2 ? 1 : s;
+    (void)BH;
+    (void)n_rows;
+    return 1;
 }
 
 // Workspace floats the split shape needs at most (any cache length up to `cap` rows).
@@ -546,7 +537,7 @@ static int launch_decode(const void* q, const void* k_new, const void* v_new, vo
                          const int32_t* len_b, const int32_t* evict_b, const int32_t* new_pos_b, hipStream_t stream)
 {
     const int n_rows = cache_len + 1;  // ragged batches pass the longest length the buffers allow
-    if (splits <= 0) splits = decode_auto_splits(B * H, n_rows);
+    if (splits <= 0 || len_b != nullptr) splits = decode_auto_splits(B * H, n_rows);  // ragged batches: fused only
     if (splits > 1 && (part == nullptr || part_floats < (size_t)B * H * splits * (D + 2))) {
         if (strict) return EC_EWORKSPACE;  // an explicit request that cannot be met
         splits = 1;                        // no workspace: the fused shape needs none
@@ -558,8 +549,7 @@ static int launch_decode(const void* q, const void* k_new, const void* v_new, vo
 #define EC_DECODE_S(W_, U_)                                                                                    \
     if (waves == W_ && unroll == U_)                                                                           \
         return launch_decode_split<DT, D, W_, U_>(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, cap, cache_len, \
-                                                  evict_idx, new_pos, scale, out, part, splits, len_b, evict_b,    \
-                                                  new_pos_b, stream);
+                                                  evict_idx, new_pos, scale, out, part, splits, stream);
         EC_DECODE_S(4, 4)
         EC_DECODE_S(8, 4)
         EC_DECODE_S(4, 8)

@@ -30,9 +30,8 @@ int score_simt_dispatch(const void* q, const void* k, const void* v, void* out, 
                         float* head_imp, int B, int H, ScoreGeom geo, const int32_t* seq_len, int D, int dt,
                         float scale, hipStream_t stream);
 int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse,
-                        float* head_imp, void* vt, int B, int H, ScoreGeom geo, const int32_t* seq_len, int D,
+                        float* head_imp, int B, int H, ScoreGeom geo, const int32_t* seq_len, int D,
                         int dt, float scale, int forced_waves, hipStream_t stream);
-size_t score_mfma_vt_bytes(int B, int H, int T, int D);
 int retention_step_launch(int32_t* n_seen_b, int32_t* cache_len_b, int32_t* evict_idx_b, int32_t* new_pos_b,
                           int32_t* pending_b, int B, int gamma_num, int gamma_den, int budget_mode, int fixed_len,
                           int trunc_mode, int recent, int n_tl, int protect_first, int flush_only, hipStream_t stream);
@@ -93,13 +92,12 @@ int score_pass(const void* q, const void* k, const void* v, void* out, float* ls
     const size_t stat_bytes = align256((size_t)B * H * geo.L * sizeof(float));
     float* ws_imp = reinterpret_cast<float*>(ws);
     float* ws_lse = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + stat_bytes);
-    void* ws_vt = reinterpret_cast<char*>(ws) + 2 * stat_bytes;
     float* lse_buf = lse ? lse : ws_lse;
     float* head_imp = (G == H) ? score : ws_imp;
 
     int rc;
     if (dt == EC_BF16)
-        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, ws_vt, B, H, geo, seq_len, D, dt, scale, 0, s);
+        rc = ec::score_mfma_dispatch(q, k, v, out, lse_buf, head_imp, B, H, geo, seq_len, D, dt, scale, 0, s);
     else
         rc = ec::score_simt_dispatch(q, k, v, out, lse_buf, head_imp, B, H, geo, seq_len, D, dt, scale, s);
     if (rc != EC_OK) return rc;
@@ -129,9 +127,8 @@ size_t ec_workspace_bytes(int fn, int B, int H, int T, int D, int dt)
     switch (fn) {
         case EC_FN_PREFILL_SCORE:
             if (!shape_supported(D, dt)) return (size_t)-1;
-            // per-head importance [B,H,T] + row log-sum-exp [B,H,T], fp32; bf16 adds a V^T copy
-            return 2 * align256((size_t)B * H * T * sizeof(float)) +
-                   (dt == EC_BF16 ? align256(ec::score_mfma_vt_bytes(B, H, T, D)) : 0);
+            // per-head importance [B,H,T] + row log-sum-exp [B,H,T], fp32
+            return 2 * align256((size_t)B * H * T * sizeof(float));
         case EC_FN_SELECT_ANCHORS: return 0;
         case EC_FN_MERGE_COMPACT: return 0;
         case EC_FN_DECODE_STEP:

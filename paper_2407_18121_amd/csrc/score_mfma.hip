@@ -2,9 +2,7 @@
 // Geometry (ScoreGeom): Tq queries over L = P + Tq key rows, query m sees rows n <= P + m; the first-turn
 // prompt pass is P = 0.
 //
-// Three kernels, none of which stores the T x T matrix:
-//   vt_transpose : V [T,D] -> V^T [D,Tp] per head (zero-padded to a multiple of 64 keys), so that
-//                  the contraction index of P.V is contiguous in memory for the MFMA operands.
+// Two kernels, neither of which stores the T x T matrix:
 //   attn_fwd     : one workgroup = 128 or 256 queries (4 or 8 waves x 32), key tiles of 64 double-
 //                  buffered in LDS.  The score tile is computed TRANSPOSED, S^T = K.Q^T, with
 //                  v_mfma_f32_32x32x16_bf16: in the accumulator layout a lane then owns one query
@@ -12,7 +10,9 @@
 //                  in-lane reductions plus one exchange between the two half-waves, the rescale
 //                  factor is a per-lane scalar, and the fp32 accumulators -- rounded to bf16 -- are
 //                  directly the B operand of O^T += V^T.P^T (the contraction index is permuted the
-//                  same way on both operands).  Emits out (optional) and the row log-sum-exp.
+//                  same way on both operands).  V tiles are staged as they lie in memory and transposed
+//                  by the LDS transpose read on their way to the registers, so no V^T copy is made.
+//                  Emits out (optional) and the row log-sum-exp.
 //   colsum       : one workgroup = 128 keys (4 waves x 32) whose K fragments stay in registers;
 //                  query tiles of 64 at or below the diagonal are streamed through LDS, S = Q.K^T
 //                  is recomputed un-transposed so that a lane owns one key (column): p =
@@ -30,14 +30,11 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;  // 16-byte staging register (native vector: stays in VGPRs)
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
 constexpr int kMfmaThreads = 256;
 constexpr int kFwdBN = 64;   // keys per LDS tile
-constexpr int kColBN = 128;  // keys per workgroup in colsum (32 per wave)
 constexpr int kColBM = 64;   // queries per LDS tile in colsum (128 measured slower: it halves the occupancy)
-constexpr int kVtPitch = kFwdBN + 8;  // bf16 elements per V^T row in LDS (144 B: conflict-free b128 reads)
-
-__host__ __device__ inline int padded_T(int T) { return (T + 63) / 64 * 64; }
 
 // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  Work
 // items are therefore renumbered so that one XCD gets a CONTIGUOUS range of items: all tiles of a
@@ -51,40 +48,14 @@ __device__ __forceinline__ int xcd_contiguous_item(int linear_id, int total)
     return (linear_id % kXcds) * per_xcd + linear_id / kXcds;  // may be >= total: caller exits
 }
 
-// ------------------------------------------------------------------ V^T
-__global__ __launch_bounds__(256) void vt_transpose_kernel(const uint16_t* __restrict__ v,
-                                                           uint16_t* __restrict__ vt, int T_max, int Tp, int D,
-                                                           int kv_rows, const int32_t* __restrict__ seq_len, int H)
-{
-    __shared__ uint16_t tile[64][64 + 2];
-    const int bh = blockIdx.z;
-    const int T = ragged_rows(seq_len, bh / H, T_max);  // rows beyond it are written as zeros
-    const int n0 = blockIdx.x * 64, d0 = blockIdx.y * 64;
-    const uint16_t* src = v + (size_t)bh * kv_rows * D;
-    uint16_t* dst = vt + (size_t)bh * D * Tp;
-    for (int i = threadIdx.x; i < 64 * 32; i += 256) {  // pairs of elements along d
-        const int r = i / 32, c = (i % 32) * 2;
-        uint32_t x = 0;
-        if (n0 + r < T) x = *reinterpret_cast<const uint32_t*>(src + (size_t)(n0 + r) * D + d0 + c);
-        tile[r][c] = (uint16_t)(x & 0xffffu);
-        tile[r][c + 1] = (uint16_t)(x >> 16);
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < 64 * 32; i += 256) {  // pairs of elements along n
-        const int d = i / 32, c = (i % 32) * 2;
-        const uint32_t x = (uint32_t)tile[c][d] | ((uint32_t)tile[c + 1][d] << 16);
-        *reinterpret_cast<uint32_t*>(dst + (size_t)(d0 + d) * Tp + n0 + c) = x;
-    }
-}
-
 // ------------------------------------------------------------------ forward
 // Double-buffered: the global loads of key tile i+1 are issued before tile i is consumed and land
 // in the other LDS buffer after it, so there is one barrier per tile and the HBM/L2 latency is
 // hidden behind the MFMA + softmax work of the current tile.
 template <int D, int WAVES>
 __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
-    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
-    uint16_t* __restrict__ out, float* __restrict__ lse, ScoreGeom geo, int Tp, float scale_log2e, int n_qtiles,
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    uint16_t* __restrict__ out, float* __restrict__ lse, ScoreGeom geo, float scale_log2e, int n_qtiles,
     int n_heads, const int32_t* __restrict__ seq_len, int H)
 {
     constexpr int THREADS = WAVES * kWave;
@@ -93,9 +64,10 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     constexpr int DB = D / 32;       // 32-row blocks of O^T
     constexpr int KP = D + 8;        // K tile pitch in elements (272 B for D=128: conflict-free b128)
     constexpr int KCH = kFwdBN * (D / 8) / THREADS;  // 16-byte chunks of the K tile per thread
-    constexpr int VCH = D * (kFwdBN / 8) / THREADS;  // 16-byte chunks of the V^T tile per thread
+    constexpr int VP = D + 16;       // V tile pitch in elements (288 B for D=128: conflict-free transposed b64 reads)
+    constexpr int VCH = kFwdBN * (D / 8) / THREADS;  // 16-byte chunks of the V tile per thread
     __shared__ __align__(16) uint16_t ks[2][kFwdBN * KP];
-    __shared__ __align__(16) uint16_t vs[2][D * kVtPitch];
+    __shared__ __align__(16) uint16_t vs[2][kFwdBN * VP];
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int c32 = lane % 32, h = lane / 32;
@@ -114,8 +86,14 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     const int m = mw + c32;                            // this lane's query
     const uint16_t* qh = q + (size_t)bh * geo.q_rows * D;
     const uint16_t* kh = k + (size_t)bh * geo.kv_rows * D;
-    const uint16_t* vth = vt + (size_t)bh * D * Tp;
+    const uint16_t* vh = v + (size_t)bh * geo.kv_rows * D;
     const bool want_out = out != nullptr;
+    // V rows sit in LDS as they are in memory (key-major); the operand of O^T += V^T.P^T needs, per lane, 8
+    // keys of ONE feature.  ds_read_b64_tr_b16 does that transposition on the way out of LDS: in a group of
+    // 16 lanes, lane r points at 4 consecutive features of key r/4 (features 4(r%4).. of the group's 16),
+    // and lane j receives feature j of keys 0..3.  Two such reads (keys +0..3, +4..7) make one 8-key
+    // fragment.  Groups 0,1 (half h = 0) take keys 0..7 of a 16-key contraction block, groups 2,3 keys 8..15.
+    const int vt_lane = ((lane / 32) * 8 + (lane % 16) / 4) * VP + ((lane / 16) % 2) * 16 + (lane % 4) * 4;
 
     bf16x8 qf[KB];
 #pragma unroll
@@ -145,8 +123,9 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 #pragma unroll
             for (int i = 0; i < VCH; ++i) {
                 const int c = tid + i * THREADS;
-                const int d = c / (kFwdBN / 8), cc = c % (kFwdBN / 8);
-                vreg[i] = *reinterpret_cast<const u32x4*>(vth + (size_t)d * Tp + n0 + cc * 8);
+                const int r = c / (D / 8), cc = c % (D / 8);
+                vreg[i] = u32x4{0u, 0u, 0u, 0u};  // rows beyond the sequence: zeros, so that 0 * padding stays 0
+                if (n0 + r < L) vreg[i] = *reinterpret_cast<const u32x4*>(vh + (size_t)(n0 + r) * D + cc * 8);
             }
         }
     };
@@ -162,8 +141,8 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 #pragma unroll
             for (int i = 0; i < VCH; ++i) {
                 const int c = tid + i * THREADS;
-                const int d = c / (kFwdBN / 8), cc = c % (kFwdBN / 8);
-                *reinterpret_cast<u32x4*>(&vs[buf][d * kVtPitch + cc * 8]) = vreg[i];
+                const int r = c / (D / 8), cc = c % (D / 8);
+                *reinterpret_cast<u32x4*>(&vs[buf][r * VP + cc * 8]) = vreg[i];
             }
         }
     };
@@ -244,14 +223,17 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 #pragma unroll
                         for (int r = 0; r < 16; ++r) o[db][r] *= corr;
                 }
-                // O^T += V^T . P^T, 16 keys per MFMA: half h contracts keys 16G + 8h .. +7 (G = kk % 2)
+                // O^T += V^T . P^T, 16 keys per MFMA: half h contracts keys 16 kk + 8h .. +7
                 bf16x8 va[4][DB];
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-                    for (int db = 0; db < DB; ++db)
-                        va[kk][db] = *reinterpret_cast<const bf16x8*>(
-                            &vs[buf][(db * 32 + c32) * kVtPitch + kk * 16 + h * 8]);
+                    for (int db = 0; db < DB; ++db) {
+                        const uint16_t* src = &vs[buf][vt_lane + (kk * 16) * VP + db * 32];
+                        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)src);
+                        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(src + 4 * VP));
+                        va[kk][db] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    }
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
                     const int nb = kk / 2, r0 = (kk % 2) * 8;
@@ -262,11 +244,11 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
                     for (int db = 0; db < DB; ++db)
                         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[kk][db], pf, o[db], 0, 0, 0);
                 }
-                __builtin_amdgcn_sched_group_barrier(0x100, 4, 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, 8, 1);
 #pragma unroll
                 for (int i = 0; i < 4 * DB - 4; ++i) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
                 }
                 __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
             }
@@ -295,36 +277,48 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 }
 
 // ------------------------------------------------------------------ column mass
-template <int D>
-__global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
+// One workgroup = 4 waves x NB blocks of 32 keys; the K fragments of a wave's keys stay in registers and every
+// Q fragment read from LDS feeds NB matrix instructions.  Work advances in steps of 32 queries.  The
+// exponentials of a step are issued between the matrix instructions of the NEXT step (the score block of a
+// step is kept "pending" for one step), so that the vector and transcendental work of one block runs while
+// the matrix pipe computes the following one.
+template <int D, int NB, bool PIPE, int MINW>
+__global__ __launch_bounds__(kMfmaThreads, MINW) void colsum_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const float* __restrict__ lse,
     float* __restrict__ head_imp, ScoreGeom geo, float scale_log2e, int n_ktiles, int n_heads,
     const int32_t* __restrict__ seq_len, int H)
 {
     constexpr int KB = D / 16;
     constexpr int QP = D + 8;
+    constexpr int KEYS_W = 32 * NB;                   // keys per wave
+    constexpr int BN = (kMfmaThreads / kWave) * KEYS_W;  // keys per workgroup
     __shared__ __align__(16) uint16_t qs[2][kColBM * QP];
     __shared__ __align__(16) float lse2[2][kColBM];  // row log-sum-exp in base-2 units
 
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // scalar: conditions on it branch, not mask
     const int c32 = lane % 32, h = lane / 32;
     const int item = xcd_contiguous_item(blockIdx.x, n_ktiles * n_heads);
     if (item >= n_ktiles * n_heads) return;
     const int bh = item / n_ktiles;
     const int Tq = ragged_rows(seq_len, bh / H, geo.Tq), P = geo.P, L = P + Tq;
-    const int n0 = (item % n_ktiles) * kColBN;  // low key tiles (most query tiles) first inside a head
+    const int n0 = (item % n_ktiles) * BN;  // low key tiles (most query tiles) first inside a head
     if (n0 >= L) return;  // ragged batch: this sequence ends before the tile (whole workgroup)
-    const int n = n0 + wave * 32 + c32;  // this lane's key
+    const int nw = n0 + wave * KEYS_W;  // first key of this wave
     const uint16_t* qh = q + (size_t)bh * geo.q_rows * D;
     const uint16_t* kh = k + (size_t)bh * geo.kv_rows * D;
     const float* lh = lse + (size_t)bh * geo.q_rows;
 
-    bf16x8 kf[KB];
+    bf16x8 kf[NB][KB];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
-        uint4 x = make_uint4(0, 0, 0, 0);
-        if (n < L) x = *reinterpret_cast<const uint4*>(kh + (size_t)n * D + kb * 16 + h * 8);
-        kf[kb] = __builtin_bit_cast(bf16x8, x);
+    for (int nb = 0; nb < NB; ++nb) {
+        const int n = nw + nb * 32 + c32;  // this lane's key in block nb
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            uint4 x = make_uint4(0, 0, 0, 0);
+            if (n < L) x = *reinterpret_cast<const uint4*>(kh + (size_t)n * D + kb * 16 + h * 8);
+            kf[nb][kb] = __builtin_bit_cast(bf16x8, x);
+        }
     }
 
     constexpr int QCH = kColBM * (D / 8) / kMfmaThreads;  // 16-byte chunks of the Q tile per thread
@@ -338,7 +332,8 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
             qreg[i] = u32x4{0u, 0u, 0u, 0u};
             if (m0 + r < Tq) qreg[i] = *reinterpret_cast<const u32x4*>(qh + (size_t)(m0 + r) * D + cc * 8);
         }
-        if (tid < kColBM) lreg = (m0 + tid < Tq) ? lh[m0 + tid] * kLog2e : INFINITY;
+        // no arithmetic on the loaded value here: using it would wait for every load just issued
+        if (tid < kColBM) lreg = (m0 + tid < Tq) ? lh[m0 + tid] : INFINITY;
     };
     auto stage = [&](int buf) {
 #pragma unroll
@@ -347,10 +342,38 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
             const int r = c / (D / 8), cc = c % (D / 8);
             *reinterpret_cast<u32x4*>(&qs[buf][r * QP + cc * 8]) = qreg[i];
         }
-        if (tid < kColBM) lse2[buf][tid] = lreg;
+        if (tid < kColBM) lse2[buf][tid] = lreg * kLog2e;
     };
 
-    float col = 0.f;
+    // the pending step: its score block, the log-sum-exp of its 16 rows of this lane, its first query.
+    // Initial values make its exponentials exact zeros (rows with lse = +inf carry no mass).
+    f32x16 sp[NB];
+    float lp[16];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sp[nb][r] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) lp[r] = INFINITY;
+    int mq_pend = 0x3fffffff;
+    float col[NB][2];  // two chains per key keep the adds off the exp latency
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) col[nb][0] = col[nb][1] = 0.f;
+
+    // exponentials of the pending step with the causal mask (steps that touch the diagonal, and the last one)
+    auto flush_masked = [&]() {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int n = nw + nb * 32 + c32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(sp[nb][r], scale_log2e, -lp[r]));
+                const int mm = mq_pend + (r / 4) * 8 + h * 4 + (r % 4);
+                col[nb][r & 1] += (P + mm >= n) ? p : 0.f;
+            }
+        }
+    };
+
     const int m_begin = (max(n0 - P, 0) / kColBM) * kColBM;  // first query tile that sees key n0 (query m sees n <= P + m)
     fetch(m_begin);
     stage(0);
@@ -360,126 +383,155 @@ __global__ __launch_bounds__(kMfmaThreads) void colsum_mfma_kernel(
         const bool more = m0 + kColBM < Tq;
         if (more) fetch(m0 + kColBM);
 
-        if (P + m0 + kColBM - 1 >= n0 + wave * 32) {  // else no query of the tile sees this wave's keys
-            constexpr int MB = kColBM / 32;  // 32-query blocks per tile
 #pragma unroll
-            for (int mp = 0; mp < MB; mp += 2) {  // two blocks at a time: two independent MFMA chains
-                f32x16 s[2];
-                bf16x8 qa[2][KB];
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
-                        qa[mb][kb] = *reinterpret_cast<const bf16x8*>(
-                            &qs[buf][((mp + mb) * 32 + c32) * QP + kb * 16 + h * 8]);
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) s[mb][r] = 0.f;
+        for (int st = 0; st < kColBM / 32; ++st) {
+            const int mq = m0 + st * 32;       // first query of this step
+            if (P + mq + 31 >= nw) {           // else no query of the step sees any of this wave's keys (wave-uniform)
+                bf16x8 qa[KB];
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb)
+                    qa[kb] = *reinterpret_cast<const bf16x8*>(&qs[buf][(st * 32 + c32) * QP + kb * 16 + h * 8]);
+                float ln[16];
 #pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
-                        s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[mb][kb], kf[kb], s[mb], 0, 0, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-                for (int i = 0; i < 2 * KB - 4; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                for (int g = 0; g < 4; ++g) {
+                    const float4 l4 = *reinterpret_cast<const float4*>(&lse2[buf][st * 32 + g * 8 + h * 4]);
+                    ln[g * 4 + 0] = l4.x;
+                    ln[g * 4 + 1] = l4.y;
+                    ln[g * 4 + 2] = l4.z;
+                    ln[g * 4 + 3] = l4.w;
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-
-                // p = exp(s - lse_row), summed down the column.  Only blocks that touch the diagonal need
-                // the causal mask; the others take the three-instruction path (fma, exp, add).
-                const int mq = m0 + mp * 32;                     // first query of this pair of blocks
-                const bool diag = P + mq < n0 + wave * 32 + 31;  // some (query, key) pair is masked
-                if (diag) {
+                f32x16 sn[NB];
 #pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
+                for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const float4 l4 =
-                                *reinterpret_cast<const float4*>(&lse2[buf][(mp + mb) * 32 + g * 8 + h * 4]);
-                            const float lr[4] = {l4.x, l4.y, l4.z, l4.w};
+                    for (int r = 0; r < 16; ++r) sn[nb][r] = 0.f;
+                if (!PIPE) {
+                    // no pending block: this step's exponentials follow its own matrix instructions; other
+                    // waves of the SIMD fill the matrix pipe meanwhile
 #pragma unroll
-                            for (int t = 0; t < 4; ++t) {
-                                const float p = __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + t], scale_log2e, -lr[t]));
-                                const int mm = mq + mb * 32 + g * 8 + h * 4 + t;
-                                col += (P + mm >= n) ? p : 0.f;  // rows beyond Tq carry lse = +inf, so p = 0
+                    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            sn[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[kb], kf[nb][kb], sn[nb], 0, 0, 0);
+                    if (P + mq < nw + KEYS_W - 1) {  // some (query, key) pair of the step is masked
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) {
+                            const int n = nw + nb * 32 + c32;
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const float p = __builtin_amdgcn_exp2f(fmaf(sn[nb][r], scale_log2e, -ln[r]));
+                                const int mm = mq + (r / 4) * 8 + h * 4 + (r % 4);
+                                col[nb][r & 1] += (P + mm >= n) ? p : 0.f;
                             }
                         }
-                } else {
-                    float c0 = 0.f, c1 = 0.f;  // two chains keep the adds off the exp latency
+                    } else {
 #pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
+                        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const float4 l4 =
-                                *reinterpret_cast<const float4*>(&lse2[buf][(mp + mb) * 32 + g * 8 + h * 4]);
-                            c0 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 0], scale_log2e, -l4.x));
-                            c1 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 1], scale_log2e, -l4.y));
-                            c0 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 2], scale_log2e, -l4.z));
-                            c1 += __builtin_amdgcn_exp2f(fmaf(s[mb][g * 4 + 3], scale_log2e, -l4.w));
-                        }
-                    col += c0 + c1;
+                            for (int r = 0; r < 16; ++r)
+                                col[nb][r & 1] += __builtin_amdgcn_exp2f(fmaf(sn[nb][r], scale_log2e, -ln[r]));
+                    }
+                    continue;
                 }
+                const bool pend_diag = P + mq_pend < nw + KEYS_W - 1;  // some (query, key) pair of the pending step is masked
+                if (pend_diag) {
+                    flush_masked();
+#pragma unroll
+                    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            sn[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[kb], kf[nb][kb], sn[nb], 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            sn[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[kb], kf[nb][kb], sn[nb], 0, 0, 0);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            col[nb][r & 1] += __builtin_amdgcn_exp2f(fmaf(sp[nb][r], scale_log2e, -lp[r]));
+                    // issue order: LDS reads run ahead, then per matrix instruction two elements' worth of
+                    // vector work (scale-and-shift, exponential, add) of the pending block
+                    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+                    for (int i = 0; i < NB * KB; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                    }
+                }
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) sp[nb] = sn[nb];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) lp[r] = ln[r];
+                mq_pend = mq;
             }
         }
         if (more) stage(buf ^ 1);
         __syncthreads();
     }
-    col += __shfl_xor(col, 32, kWave);
-    if (h == 0 && n < L) head_imp[(size_t)bh * geo.imp_rows + n] = col;
+    if (PIPE) flush_masked();
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        float c = col[nb][0] + col[nb][1];
+        c += __shfl_xor(c, 32, kWave);
+        const int n = nw + nb * 32 + c32;
+        if (h == 0 && n < L) head_imp[(size_t)bh * geo.imp_rows + n] = c;
+    }
 }
 
 template <int D>
 static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse,
-                       float* head_imp, uint16_t* vt, int B, int H, ScoreGeom geo, const int32_t* seq_len, float scale,
+                       float* head_imp, int B, int H, ScoreGeom geo, const int32_t* seq_len, float scale,
                        int forced_waves, hipStream_t stream)
 {
     const float sl = scale * kLog2e;
     const int Tq = geo.Tq, L = geo.L;
-    const int Lp = padded_T(L);
     const int BH = B * H;
-    if (out != nullptr) {
-        hipLaunchKernelGGL(vt_transpose_kernel, dim3(Lp / 64, D / 64, BH), dim3(256), 0, stream, v, vt, L, Lp, D,
-                           geo.kv_rows, seq_len, H);
-        int rc = status_from_hip(hipGetLastError());
-        if (rc != EC_OK) return rc;
-    }
     // 8-wave workgroups (256 queries) halve the LDS staging per flop, which pays once the key loop is long
     // (measured crossover between 2048 and 3072 keys); 4-wave ones balance shorter prompts better
     int waves = forced_waves;
     if (waves != 4 && waves != 8) waves = (L >= 2560 && (long long)BH * ((Tq + 255) / 256) >= 512) ? 8 : 4;
     if (waves == 8)
         hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 8>), dim3(xcd_grid(((Tq + 255) / 256) * BH)), dim3(512), 0,
-                           stream, q, k, vt, out, lse, geo, Lp, sl, (Tq + 255) / 256, BH, seq_len, H);
+                           stream, q, k, v, out, lse, geo, sl, (Tq + 255) / 256, BH, seq_len, H);
     else
         hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 4>), dim3(xcd_grid(((Tq + 127) / 128) * BH)), dim3(256), 0,
-                           stream, q, k, vt, out, lse, geo, Lp, sl, (Tq + 127) / 128, BH, seq_len, H);
+                           stream, q, k, v, out, lse, geo, sl, (Tq + 127) / 128, BH, seq_len, H);
     int rc = status_from_hip(hipGetLastError());
     if (rc != EC_OK) return rc;
-    hipLaunchKernelGGL((colsum_mfma_kernel<D>), dim3(xcd_grid(((L + kColBN - 1) / kColBN) * BH)),
-                       dim3(kMfmaThreads), 0, stream, q, k, lse, head_imp, geo, sl, (L + kColBN - 1) / kColBN, BH,
-                       seq_len, H);
+    // 64 keys per wave halve the LDS reads per matrix instruction; 32 keep twice as many workgroups for
+    // shapes that would otherwise leave compute units idle
+    const int kt256 = (L + 255) / 256, kt128 = (L + 127) / 128;
+#define EC_COLSUM(NB_, PIPE_, MINW_, KT_)                                                                        \
+    hipLaunchKernelGGL((colsum_mfma_kernel<D, NB_, PIPE_, MINW_>), dim3(xcd_grid(KT_ * BH)), dim3(kMfmaThreads), 0, \
+                       stream, q, k, lse, head_imp, geo, sl, KT_, BH, seq_len, H)
+    // measured (B4 H32 T8192 / B8 H32 T2048): 64 keys per wave with the pending-block pipeline 1165 / 223 us,
+    // 32 keys per wave without it at four waves per SIMD 1272 / 202 us
+    if ((long long)kt256 * BH >= 4096)
+        EC_COLSUM(2, true, 2, kt256);
+    else
+        EC_COLSUM(1, false, 4, kt128);
+#undef EC_COLSUM
     return status_from_hip(hipGetLastError());
 }
 
-// bytes of workspace the V^T copy needs (T = number of key rows)
-size_t score_mfma_vt_bytes(int B, int H, int T, int D) { return (size_t)B * H * D * padded_T(T) * sizeof(uint16_t); }
-
-// Per-head importance into head_imp [B,H,L]; out may be NULL (then vt is not touched).
+// Per-head importance into head_imp [B,H,L]; out may be NULL (then v is not read).
 int score_mfma_dispatch(const void* q, const void* k, const void* v, void* out, float* lse, float* head_imp,
-                        void* vt, int B, int H, ScoreGeom geo, const int32_t* seq_len, int D, int dt, float scale,
+                        int B, int H, ScoreGeom geo, const int32_t* seq_len, int D, int dt, float scale,
                         int forced_waves, hipStream_t stream)
 {
     if (dt != EC_BF16) return EC_EUNSUPPORTED;
     if (D == 128)
         return launch_mfma<128>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out, lse,
-                                head_imp, (uint16_t*)vt, B, H, geo, seq_len, scale, forced_waves, stream);
+                                head_imp, B, H, geo, seq_len, scale, forced_waves, stream);
     if (D == 64)
         return launch_mfma<64>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out, lse,
-                               head_imp, (uint16_t*)vt, B, H, geo, seq_len, scale, forced_waves, stream);
+                               head_imp, B, H, geo, seq_len, scale, forced_waves, stream);
     return EC_EUNSUPPORTED;
 }
 

@@ -98,10 +98,7 @@ def test_prefill_chain_ragged(dtype, D, H, Gmode, lens):
     (3, 3, 700, [655, 300, 64], [0, 275, -1]),
     (2, 1, 1100, [1029, 1099, 96, 500], [600, 1074, 71, -1]),
 ])
-@pytest.mark.parametrize("with_ws", [False, True])
-def test_decode_step_ragged(dtype, D, H, G, cap, lens, victims, with_ws):
-    """with_ws: the workspace ec_decode_step asks for is passed, so that (these batches being small) every
-    sequence's rows are divided over several workgroups according to its own length."""
+def test_decode_step_ragged(dtype, D, H, G, cap, lens, victims):
     B = len(lens)
     rng = np.random.default_rng(cap + B + D)
     scale = 1.0 / np.sqrt(D)
@@ -116,11 +113,8 @@ def test_decode_step_ragged(dtype, D, H, G, cap, lens, victims, with_ws):
         dkc[b, :, n:] = float("nan")
         dvc[b, :, n:] = float("nan")
     dout = torch.full((B, H, D), float("nan"), dtype=torch_dtype(dtype), device="cuda")
-    ws = ec.new_workspace(ec.EC_FN_DECODE_STEP, B, H, cap, D, ec.dtype_code(dkc)) if with_ws else None
-    if with_ws:
-        ws.fill_(0xFF)
     ec.ec_decode_step_varlen(to_dev(q, dtype), to_dev(kn, dtype), to_dev(vn, dtype), dkc, dvc, dpos, _i32(lens),
-                             _i32(victims), _i32(new_pos), scale, dout, ws=ws)
+                             _i32(victims), _i32(new_pos), scale, dout)
     torch.cuda.synchronize()
     for b, (n, vic) in enumerate(zip(lens, victims)):
         okc, ovc, opos = kc[b:b + 1].astype(np.float64), vc[b:b + 1].astype(np.float64), pos[b:b + 1].copy()
