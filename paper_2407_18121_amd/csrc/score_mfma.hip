@@ -69,7 +69,8 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     __shared__ __align__(16) uint16_t ks[2][kFwdBN * KP];
     __shared__ __align__(16) uint16_t vs[2][kFwdBN * VP];
 
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // scalar: tile skips branch instead of masking
     const int c32 = lane % 32, h = lane / 32;
     // LDS row j of the K tile holds key swap23(j) (bits 2 and 3 of the row number exchanged), i.e. row
     // i of a 32-key S^T block is key 16(i/16) + 8((i/4)%2) + 4((i/8)%2) + i%4.  In the accumulator
@@ -200,7 +201,11 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
             for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[nb][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * scale_log2e;
+            {   // the other half-wave holds the other 32 keys of each query: exchange through the lane-swap
+                // instruction (a shuffle would go through LDS and its latency sits on the critical path)
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * scale_log2e;
+            }
             const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every query
             const bool grew = m_new > m_run;
             const float corr = __builtin_amdgcn_exp2f(m_run - m_new);  // exp2(-inf) = 0 on the first tile
