@@ -123,6 +123,60 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
             }
         }
     };
+    // The share of one lane group in a bucket that the whole workgroup sums: rows first, first + step, ...
+    // A slot is loaded again as soon as its row has been added, so the loads in flight do not drain
+    // between rounds.  The additions are made in the order of stream().
+    auto stream_ring = [&](int first, int hi, int step) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc_k[e] = acc_v[e] = 0.f;
+        wsum = 0;
+        uint4 ck[kMergeUnroll], cv[kMergeUnroll];
+        int wt[kMergeUnroll];
+#pragma unroll
+        for (int u = 0; u < kMergeUnroll; ++u) {
+            const int r = first + u * step;
+            ck[u] = make_uint4(0, 0, 0, 0);
+            cv[u] = make_uint4(0, 0, 0, 0);
+            wt[u] = 1;
+            if (r <= hi) {
+                if (WEIGHTED) wt[u] = max(wrow[r], 1);
+                ck[u] = load_stream(src_k + (size_t)r * LPR);
+                cv[u] = load_stream(src_v + (size_t)r * LPR);
+            }
+        }
+        for (int t = first; t <= hi; t += kMergeUnroll * step) {
+#pragma unroll
+            for (int u = 0; u < kMergeUnroll; ++u) {
+                const int r = t + u * step;
+                if (r <= hi) {
+                    float xk[EPL], xv[EPL];
+                    unpack<DT>(ck[u], xk);
+                    unpack<DT>(cv[u], xv);
+                    if (WEIGHTED) {
+                        wsum += wt[u];
+                        const float w = (float)wt[u];
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) {
+                            acc_k[e] = fmaf(w, xk[e], acc_k[e]);
+                            acc_v[e] = fmaf(w, xv[e], acc_v[e]);
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) {
+                            acc_k[e] += xk[e];
+                            acc_v[e] += xv[e];
+                        }
+                    }
+                    const int rn = r + kMergeUnroll * step;
+                    if (rn <= hi) {
+                        if (WEIGHTED) wt[u] = max(wrow[rn], 1);
+                        ck[u] = load_stream(src_k + (size_t)rn * LPR);
+                        cv[u] = load_stream(src_v + (size_t)rn * LPR);
+                    }
+                }
+            }
+        }
+    };
     // divide by the count, round once, store cache row jj and its bookkeeping
     auto finish = [&](int jj, int n_rows, int w_total) {
         const int count = WEIGHTED ? w_total : n_rows;
@@ -174,7 +228,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_compact_kernel(
         const int jj = chunk * GROUPS + sh_long[i];
         int llo, lhi;
         bucket_bounds(a, jj, n_anchor, T, llo, lhi);
-        stream(llo + grp, lhi, GROUPS, false);
+        stream_ring(llo + grp, lhi, GROUPS);
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
             sh_part[grp][(sub * EPL + e) * 2] = acc_k[e];
