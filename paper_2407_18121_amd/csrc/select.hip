@@ -24,26 +24,6 @@ __device__ __forceinline__ uint32_t score_key(float s)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Exclusive prefix of a per-thread flag over the workgroup; returns the total in `total`.
-__device__ __forceinline__ int block_excl_scan_flag(bool flag, int* wave_tot /*[kSelWaves]*/, int& total)
-{
-    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    const unsigned long long ball = __ballot(flag);
-    const int in_wave = __popcll(ball & ((1ull << lane) - 1ull));
-    __syncthreads();  // previous users of wave_tot are done
-    if (lane == 0) wave_tot[wave] = __popcll(ball);
-    __syncthreads();
-    int before = 0, tot = 0;
-#pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) {
-        const int c = wave_tot[w];
-        before += (w < wave) ? c : 0;
-        tot += c;
-    }
-    total = tot;
-    return before + in_wave;
-}
-
 // Ragged batches: seq_len[b] positions and n_anchor_b[b] anchors for batch element b (both clamped), rows
 // of score and anchor_idx stay T_max and n_max apart.
 __global__ __launch_bounds__(kSelThreads) void select_anchors_kernel(
@@ -53,12 +33,12 @@ __global__ __launch_bounds__(kSelThreads) void select_anchors_kernel(
 {
     extern __shared__ uint32_t lds_keys[];
     __shared__ int hist[256];
-    __shared__ int suffix[256];
-    __shared__ int wave_tot[kSelWaves];
+    __shared__ int wave_tot[2][kSelWaves];  // two sets, used in turn: one barrier per sweep step
     __shared__ uint32_t sh_prefix;
     __shared__ int sh_need;
 
     const int tid = threadIdx.x;
+    const int lane = tid % kWave, wave = tid / kWave;
     const int b = blockIdx.x / G;
     const int T = ragged_rows(seq_len, b, T_max);
     const int n_anchor = n_anchor_b ? min(max(n_anchor_b[b], 0), min(T, n_max)) : n_max;
@@ -72,6 +52,7 @@ __global__ __launch_bounds__(kSelThreads) void select_anchors_kernel(
 
     if (keys_in_lds)
         for (int t = tid; t < T; t += kSelThreads) lds_keys[t] = score_key(s[t]);
+    if (tid < 256) hist[tid] = 0;
     if (tid == 0) {
         sh_prefix = 0u;
         sh_need = n_free;
@@ -83,8 +64,6 @@ __global__ __launch_bounds__(kSelThreads) void select_anchors_kernel(
         for (int pass = 0; pass < 4; ++pass) {
             const int shift = 24 - 8 * pass;
             const uint32_t hi_mask = (pass == 0) ? 0u : (0xffffffffu << (shift + 8));
-            if (tid < 256) hist[tid] = 0;
-            __syncthreads();
             const uint32_t prefix = sh_prefix;
             const int need = sh_need;
             for (int t = free_lo + tid; t < free_hi; t += kSelThreads) {
@@ -92,21 +71,29 @@ __global__ __launch_bounds__(kSelThreads) void select_anchors_kernel(
                 if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xffu], 1);
             }
             __syncthreads();
-            // suffix[d] = number of candidates with digit > d  (inclusive scan from the top)
-            if (tid < 256) suffix[tid] = hist[tid];
-            __syncthreads();
-            for (int off = 1; off < 256; off <<= 1) {
-                int add = 0;
-                if (tid < 256 && tid + off < 256) add = suffix[tid + off];
-                __syncthreads();
-                if (tid < 256) suffix[tid] += add;
-                __syncthreads();
-            }
-            if (tid < 256) {
-                const int above = suffix[tid] - hist[tid];  // candidates with a larger digit
-                if (above < need && need <= suffix[tid]) {  // exactly one digit satisfies this
-                    sh_prefix = prefix | ((uint32_t)tid << shift);
-                    sh_need = need - above;
+            // One wave finds the digit: lane l owns digits 4l..4l+3; a shuffle scan from the top gives the
+            // number of candidates in the lanes above, and the four digits of a lane are walked in registers.
+            if (wave == 0) {
+                int c[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) c[i] = hist[4 * lane + i];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) hist[4 * lane + i] = 0;  // ready for the next pass
+                const int mine = c[0] + c[1] + c[2] + c[3];
+                int incl = mine;  // candidates in lanes >= this one
+#pragma unroll
+                for (int off = 1; off < kWave; off <<= 1) {
+                    const int x = __shfl_down(incl, off, kWave);
+                    if (lane + off < kWave) incl += x;
+                }
+                int above = incl - mine;  // candidates with a digit above this lane's four
+#pragma unroll
+                for (int i = 3; i >= 0; --i) {
+                    if (above < need && need <= above + c[i]) {  // exactly one digit satisfies this
+                        sh_prefix = prefix | ((uint32_t)(4 * lane + i) << shift);
+                        sh_need = need - above;
+                    }
+                    above += c[i];
                 }
             }
             __syncthreads();
@@ -116,25 +103,39 @@ __global__ __launch_bounds__(kSelThreads) void select_anchors_kernel(
     const int need_eq = sh_need;     // how many elements equal to kth are selected (lowest positions)
 
     // ---- ordered emission ----
-    int base_eq = 0, base_out = 0;
-    for (int t0 = 0; t0 < T; t0 += kSelThreads) {
+    // One workgroup scan per 1024 positions carries two counts, packed into one word: elements that are
+    // kept outright (protected or above the threshold key) and elements equal to it.  Of the equal ones the
+    // first need_eq are kept, so an element's output slot is (kept outright before it) + min(equal before
+    // it, need_eq).
+    int base_keep = 0, base_eq = 0, set = 0;
+    for (int t0 = 0; t0 < T; t0 += kSelThreads, set ^= 1) {
         const int t = t0 + tid;
-        bool prot = false, gt = false, eq = false;
+        bool keep = false, eq = false;
         if (t < T) {
-            prot = (t < free_lo) || (t >= free_hi);
-            if (!prot && n_free > 0) {
+            keep = (t < free_lo) || (t >= free_hi);
+            if (!keep && n_free > 0) {
                 const uint32_t key = keys_in_lds ? lds_keys[t] : score_key(s[t]);
-                gt = key > kth;
+                keep = key > kth;
                 eq = key == kth;
             }
         }
-        int tot_eq, tot_out;
-        const int eq_rank = base_eq + block_excl_scan_flag(eq, wave_tot, tot_eq);
-        const bool sel = prot || gt || (eq && eq_rank < need_eq);
-        const int o = base_out + block_excl_scan_flag(sel, wave_tot, tot_out);
-        if (sel && o < n_anchor) dst[o] = t;
-        base_eq += tot_eq;
-        base_out += tot_out;
+        const unsigned long long ball_keep = __ballot(keep), ball_eq = __ballot(eq);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        if (lane == 0) wave_tot[set][wave] = __popcll(ball_keep) | (__popcll(ball_eq) << 16);
+        __syncthreads();
+        int before = 0, tot = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) {
+            const int c = wave_tot[set][w];
+            before += (w < wave) ? c : 0;
+            tot += c;
+        }
+        const int keep_before = base_keep + (before & 0xffff) + __popcll(ball_keep & below);
+        const int eq_before = base_eq + (before >> 16) + __popcll(ball_eq & below);
+        const int o = keep_before + min(eq_before, need_eq);
+        if ((keep || (eq && eq_before < need_eq)) && o < n_anchor) dst[o] = t;
+        base_keep += tot & 0xffff;
+        base_eq += tot >> 16;
     }
 }
 
