@@ -48,6 +48,19 @@ __device__ __forceinline__ int xcd_contiguous_item(int linear_id, int total)
     return (linear_id % kXcds) * per_xcd + linear_id / kXcds;  // may be >= total: caller exits
 }
 
+// Buffer descriptor over `bytes` bytes at p (raw: no stride, 32-bit data format).  Loads through it whose byte
+// offset is at or beyond `bytes` return zeros instead of touching memory.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* p, int bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+// The whole offset travels in the vector operand: the bounds check of this hardware generation does not see
+// the scalar offset.
+__device__ __forceinline__ u32x4 buffer_load_16(__amdgpu_buffer_rsrc_t rsrc, int byte_offset)
+{
+    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset, 0, 0));
+}
+
 // ------------------------------------------------------------------ forward
 // Double-buffered: the global loads of key tile i+1 are issued before tile i is consumed and land
 // in the other LDS buffer after it, so there is one barrier per tile and the HBM/L2 latency is
@@ -111,23 +124,19 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
         for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;  // l_run: this half-wave's share of the row sum
 
+    // K and V tiles are fetched through buffer descriptors that end at the sequence's last row: a 16-byte
+    // chunk beyond it comes back as zeros from the address unit itself (no compare, no branch, and 0 * padding
+    // stays 0 for V), and the per-thread offset is one add per tile.
+    const __amdgpu_buffer_rsrc_t k_rsrc = tile_rsrc(kh, L * D * 2);
+    const __amdgpu_buffer_rsrc_t v_rsrc = tile_rsrc(vh, L * D * 2);
     u32x4 kreg[KCH], vreg[VCH];
     auto fetch = [&](int n0) {
+        const int off = n0 * (D * 2) + tid * 16;  // chunk c = tid + i THREADS of the tile sits 16 c bytes into it
 #pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            const int c = tid + i * THREADS;
-            const int r = c / (D / 8), cc = c % (D / 8);
-            kreg[i] = u32x4{0u, 0u, 0u, 0u};
-            if (n0 + r < L) kreg[i] = *reinterpret_cast<const u32x4*>(kh + (size_t)(n0 + r) * D + cc * 8);
-        }
+        for (int i = 0; i < KCH; ++i) kreg[i] = buffer_load_16(k_rsrc, off + i * THREADS * 16);
         if (want_out) {
 #pragma unroll
-            for (int i = 0; i < VCH; ++i) {
-                const int c = tid + i * THREADS;
-                const int r = c / (D / 8), cc = c % (D / 8);
-                vreg[i] = u32x4{0u, 0u, 0u, 0u};  // rows beyond the sequence: zeros, so that 0 * padding stays 0
-                if (n0 + r < L) vreg[i] = *reinterpret_cast<const u32x4*>(vh + (size_t)(n0 + r) * D + cc * 8);
-            }
+            for (int i = 0; i < VCH; ++i) vreg[i] = buffer_load_16(v_rsrc, off + i * THREADS * 16);
         }
     };
     auto stage = [&](int buf) {
@@ -329,14 +338,11 @@ __global__ __launch_bounds__(kMfmaThreads, MINW) void colsum_mfma_kernel(
     constexpr int QCH = kColBM * (D / 8) / kMfmaThreads;  // 16-byte chunks of the Q tile per thread
     u32x4 qreg[QCH];
     float lreg = 0.f;
+    const __amdgpu_buffer_rsrc_t q_rsrc = tile_rsrc(qh, Tq * D * 2);  // queries beyond the sequence read as zeros
     auto fetch = [&](int m0) {
+        const int off = m0 * (D * 2) + tid * 16;
 #pragma unroll
-        for (int i = 0; i < QCH; ++i) {
-            const int c = tid + i * kMfmaThreads;
-            const int r = c / (D / 8), cc = c % (D / 8);
-            qreg[i] = u32x4{0u, 0u, 0u, 0u};
-            if (m0 + r < Tq) qreg[i] = *reinterpret_cast<const u32x4*>(qh + (size_t)(m0 + r) * D + cc * 8);
-        }
+        for (int i = 0; i < QCH; ++i) qreg[i] = buffer_load_16(q_rsrc, off + i * kMfmaThreads * 16);
         // no arithmetic on the loaded value here: using it would wait for every load just issued
         if (tid < kColBM) lreg = (m0 + tid < Tq) ? lh[m0 + tid] : INFINITY;
     };
