@@ -77,7 +77,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     constexpr int DB = D / 32;       // 32-row blocks of O^T
     constexpr int KP = D + 8;        // K tile pitch in elements (272 B for D=128: conflict-free b128)
     constexpr int KCH = kFwdBN * (D / 8) / THREADS;  // 16-byte chunks of the K tile per thread
-    constexpr int VP = D + 16;       // V tile pitch in elements (288 B for D=128: conflict-free transposed b64 reads)
+    constexpr int VP = D + 32;       // V tile pitch in elements (320 B for D=128: the transposed b64 reads measure conflict-free)
     constexpr int VCH = kFwdBN * (D / 8) / THREADS;  // 16-byte chunks of the V tile per thread
     __shared__ __align__(16) uint16_t ks[2][kFwdBN * KP];
     __shared__ __align__(16) uint16_t vs[2][kFwdBN * VP];
@@ -356,31 +356,89 @@ __global__ __launch_bounds__(kMfmaThreads, MINW) void colsum_mfma_kernel(
         if (tid < kColBM) lse2[buf][tid] = lreg * kLog2e;
     };
 
-    // the pending step: its score block, the log-sum-exp of its 16 rows of this lane, its first query.
-    // Initial values make its exponentials exact zeros (rows with lse = +inf carry no mass).
-    f32x16 sp[NB];
-    float lp[16];
+    // PIPE: a step's score block stays "pending" for one step and its exponentials are issued between the
+    // matrix instructions of the next one.  Two register sets, A and B, take turns: the first step of a query
+    // tile computes into A while B is pending, the second into B while A is pending, so no block is ever
+    // copied.  B's initial values make its exponentials exact zeros (rows with lse = +inf carry no mass).
+    f32x16 sA[NB], sB[NB];
+    float lA[16], lB[16];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sp[nb][r] = 0.f;
+        for (int r = 0; r < 16; ++r) sA[nb][r] = sB[nb][r] = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) lp[r] = INFINITY;
-    int mq_pend = 0x3fffffff;
+    for (int r = 0; r < 16; ++r) lA[r] = lB[r] = INFINITY;
+    int mq_pend = 0x3fffffff;  // first query of the step pending in B between tiles
     float col[NB][2];  // two chains per key keep the adds off the exp latency
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) col[nb][0] = col[nb][1] = 0.f;
 
-    // exponentials of the pending step with the causal mask (steps that touch the diagonal, and the last one)
-    auto flush_masked = [&]() {
+    // exponentials of a block with the causal mask (steps that touch the diagonal, and the last one)
+    auto exp_masked = [&](const f32x16 (&sx)[NB], const float (&lx)[16], int mq) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int n = nw + nb * 32 + c32;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(sp[nb][r], scale_log2e, -lp[r]));
-                const int mm = mq_pend + (r / 4) * 8 + h * 4 + (r % 4);
+                const float p = __builtin_amdgcn_exp2f(fmaf(sx[nb][r], scale_log2e, -lx[r]));
+                const int mm = mq + (r / 4) * 8 + h * 4 + (r % 4);
                 col[nb][r & 1] += (P + mm >= n) ? p : 0.f;
+            }
+        }
+    };
+    auto exp_plain = [&](const f32x16 (&sx)[NB], const float (&lx)[16]) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                col[nb][r & 1] += __builtin_amdgcn_exp2f(fmaf(sx[nb][r], scale_log2e, -lx[r]));
+    };
+    // S = Q.K^T of the 32 queries of step st into sn, their log-sum-exp into ln
+    auto load_q = [&](int buf, int st, bf16x8 (&qa)[KB], float (&ln)[16]) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+            qa[kb] = *reinterpret_cast<const bf16x8*>(&qs[buf][(st * 32 + c32) * QP + kb * 16 + h * 8]);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float4 l4 = *reinterpret_cast<const float4*>(&lse2[buf][st * 32 + g * 8 + h * 4]);
+            ln[g * 4 + 0] = l4.x;
+            ln[g * 4 + 1] = l4.y;
+            ln[g * 4 + 2] = l4.z;
+            ln[g * 4 + 3] = l4.w;
+        }
+    };
+    auto mfmas = [&](const bf16x8 (&qa)[KB], f32x16 (&sn)[NB]) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sn[nb][r] = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                sn[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[kb], kf[nb][kb], sn[nb], 0, 0, 0);
+    };
+    // one pipelined step: sn, ln <- step st of the tile; the pending block (sp, lp, first query mqp) is retired
+    auto piped_step = [&](int buf, int st, f32x16 (&sn)[NB], float (&ln)[16], const f32x16 (&sp)[NB],
+                          const float (&lp)[16], int mqp) {
+        bf16x8 qa[KB];
+        load_q(buf, st, qa, ln);
+        if (P + mqp < nw + KEYS_W - 1) {  // some (query, key) pair of the pending step is masked
+            exp_masked(sp, lp, mqp);
+            mfmas(qa, sn);
+        } else {
+            mfmas(qa, sn);
+            exp_plain(sp, lp);
+            // issue order: LDS reads run ahead, then per matrix instruction two elements' worth of vector
+            // work (scale-and-shift, exponential, add) of the pending block
+            __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+            for (int i = 0; i < NB * KB; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
             }
         }
     };
@@ -394,98 +452,36 @@ __global__ __launch_bounds__(kMfmaThreads, MINW) void colsum_mfma_kernel(
         const bool more = m0 + kColBM < Tq;
         if (more) fetch(m0 + kColBM);
 
+        if (PIPE) {
+            // a tile takes part as soon as one of its queries sees one of this wave's keys (wave-uniform); a
+            // step of it that sees none is masked away like the diagonal
+            if (P + m0 + kColBM - 1 >= nw) {
+                static_assert(kColBM == 64, "two steps per query tile");
+                piped_step(buf, 0, sA, lA, sB, lB, mq_pend);
+                piped_step(buf, 1, sB, lB, sA, lA, m0);
+                mq_pend = m0 + 32;
+            }
+        } else {
 #pragma unroll
-        for (int st = 0; st < kColBM / 32; ++st) {
-            const int mq = m0 + st * 32;       // first query of this step
-            if (P + mq + 31 >= nw) {           // else no query of the step sees any of this wave's keys (wave-uniform)
-                bf16x8 qa[KB];
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
-                    qa[kb] = *reinterpret_cast<const bf16x8*>(&qs[buf][(st * 32 + c32) * QP + kb * 16 + h * 8]);
-                float ln[16];
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 l4 = *reinterpret_cast<const float4*>(&lse2[buf][st * 32 + g * 8 + h * 4]);
-                    ln[g * 4 + 0] = l4.x;
-                    ln[g * 4 + 1] = l4.y;
-                    ln[g * 4 + 2] = l4.z;
-                    ln[g * 4 + 3] = l4.w;
-                }
-                f32x16 sn[NB];
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sn[nb][r] = 0.f;
-                if (!PIPE) {
+            for (int st = 0; st < kColBM / 32; ++st) {
+                const int mq = m0 + st * 32;  // first query of this step
+                if (P + mq + 31 >= nw) {      // else no query of the step sees any of this wave's keys (wave-uniform)
                     // no pending block: this step's exponentials follow its own matrix instructions; other
                     // waves of the SIMD fill the matrix pipe meanwhile
-#pragma unroll
-                    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-                            sn[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[kb], kf[nb][kb], sn[nb], 0, 0, 0);
-                    if (P + mq < nw + KEYS_W - 1) {  // some (query, key) pair of the step is masked
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb) {
-                            const int n = nw + nb * 32 + c32;
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                const float p = __builtin_amdgcn_exp2f(fmaf(sn[nb][r], scale_log2e, -ln[r]));
-                                const int mm = mq + (r / 4) * 8 + h * 4 + (r % 4);
-                                col[nb][r & 1] += (P + mm >= n) ? p : 0.f;
-                            }
-                        }
-                    } else {
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                            for (int r = 0; r < 16; ++r)
-                                col[nb][r & 1] += __builtin_amdgcn_exp2f(fmaf(sn[nb][r], scale_log2e, -ln[r]));
-                    }
-                    continue;
+                    bf16x8 qa[KB];
+                    load_q(buf, st, qa, lA);
+                    mfmas(qa, sA);
+                    if (P + mq < nw + KEYS_W - 1)  // some (query, key) pair of the step is masked
+                        exp_masked(sA, lA, mq);
+                    else
+                        exp_plain(sA, lA);
                 }
-                const bool pend_diag = P + mq_pend < nw + KEYS_W - 1;  // some (query, key) pair of the pending step is masked
-                if (pend_diag) {
-                    flush_masked();
-#pragma unroll
-                    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-                            sn[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[kb], kf[nb][kb], sn[nb], 0, 0, 0);
-                } else {
-#pragma unroll
-                    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-                            sn[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[kb], kf[nb][kb], sn[nb], 0, 0, 0);
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            col[nb][r & 1] += __builtin_amdgcn_exp2f(fmaf(sp[nb][r], scale_log2e, -lp[r]));
-                    // issue order: LDS reads run ahead, then per matrix instruction two elements' worth of
-                    // vector work (scale-and-shift, exponential, add) of the pending block
-                    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
-#pragma unroll
-                    for (int i = 0; i < NB * KB; ++i) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-                    }
-                }
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) sp[nb] = sn[nb];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) lp[r] = ln[r];
-                mq_pend = mq;
             }
         }
         if (more) stage(buf ^ 1);
         __syncthreads();
     }
-    if (PIPE) flush_masked();
+    if (PIPE) exp_masked(sB, lB, mq_pend);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         float c = col[nb][0] + col[nb][1];
