@@ -34,6 +34,7 @@ typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
 constexpr int kMfmaThreads = 256;
 constexpr int kFwdBN = 64;   // keys per LDS tile
+constexpr int kSplitMaxWorkgroups = 256;  // launches of at most this many workgroups split one workgroup's loop over two wave groups
 constexpr int kColBM = 64;   // queries per LDS tile in colsum (128 measured slower: it halves the occupancy)
 
 // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  Work
@@ -65,25 +66,35 @@ __device__ __forceinline__ u32x4 buffer_load_16(__amdgpu_buffer_rsrc_t rsrc, int
 // Double-buffered: the global loads of key tile i+1 are issued before tile i is consumed and land
 // in the other LDS buffer after it, so there is one barrier per tile and the HBM/L2 latency is
 // hidden behind the MFMA + softmax work of the current tile.
-template <int D, int WAVES>
+// KSPLIT = 2 (short prompts that give the chip one workgroup per compute unit or less): the 8 waves form two
+// groups of 4 that share the workgroup's 128 queries and take alternate key tiles, each group staging its own
+// tiles; their (max, sum, O) are merged through LDS at the end.  The key loop of a workgroup, which is what
+// bounds such launches, is half as long, and every SIMD has two waves.
+template <int D, int WAVES, int KSPLIT>
 __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     uint16_t* __restrict__ out, float* __restrict__ lse, ScoreGeom geo, float scale_log2e, int n_qtiles,
     int n_heads, const int32_t* __restrict__ seq_len, int H)
 {
-    constexpr int THREADS = WAVES * kWave;
-    constexpr int BM = WAVES * 32;   // queries per workgroup
+    constexpr int GW = WAVES / KSPLIT;  // waves of one group: one per 32 queries
+    constexpr int THREADS = GW * kWave; // threads that stage one tile together
+    constexpr int BM = GW * 32;      // queries per workgroup
     constexpr int KB = D / 16;       // contraction blocks of Q.K
     constexpr int DB = D / 32;       // 32-row blocks of O^T
     constexpr int KP = D + 8;        // K tile pitch in elements (272 B for D=128: conflict-free b128)
     constexpr int KCH = kFwdBN * (D / 8) / THREADS;  // 16-byte chunks of the K tile per thread
     constexpr int VP = D + 32;       // V tile pitch in elements (320 B for D=128: the transposed b64 reads measure conflict-free)
     constexpr int VCH = kFwdBN * (D / 8) / THREADS;  // 16-byte chunks of the V tile per thread
-    __shared__ __align__(16) uint16_t ks[2][kFwdBN * KP];
-    __shared__ __align__(16) uint16_t vs[2][kFwdBN * VP];
+    __shared__ __align__(16) uint16_t ks_all[KSPLIT][2][kFwdBN * KP];
+    __shared__ __align__(16) uint16_t vs_all[KSPLIT][2][kFwdBN * VP];
 
-    const int tid = threadIdx.x, lane = tid % kWave;
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // scalar: tile skips branch instead of masking
+    const int lane = threadIdx.x % kWave;
+    const int wave_wg = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int grp = wave_wg / GW;    // scalar: which key tiles (tile number mod KSPLIT)
+    const int wave = wave_wg % GW;   // scalar: which 32 queries; tile skips branch instead of masking
+    const int tid = threadIdx.x % THREADS;
+    uint16_t (*ks)[kFwdBN * KP] = ks_all[grp];
+    uint16_t (*vs)[kFwdBN * VP] = vs_all[grp];
     const int c32 = lane % 32, h = lane / 32;
     // LDS row j of the K tile holds key swap23(j) (bits 2 and 3 of the row number exchanged), i.e. row
     // i of a 32-key S^T block is key 16(i/16) + 8((i/4)%2) + 4((i/8)%2) + i%4.  In the accumulator
@@ -122,7 +133,10 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;  // l_run: this half-wave's share of the row sum
+    // l_run: this half-wave's share of the row sum.  A group that does not start at key 0 can meet a tile in
+    // which a query sees no key at all; a finite floor for the running maximum keeps exp2(-inf - m) at zero
+    // there instead of exp2(-inf + inf).
+    float m_run = (KSPLIT == 1) ? -INFINITY : -1e30f, l_run = 0.f;
 
     // K and V tiles are fetched through buffer descriptors that end at the sequence's last row: a 16-byte
     // chunk beyond it comes back as zeros from the address unit itself (no compare, no branch, and 0 * padding
@@ -158,15 +172,17 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
     };
 
     const int n_end = min(L, P + m0 + BM);  // the workgroup's last query sees rows up to P + m0 + BM - 1
-    fetch(0);
+    const int n_iter = ((n_end + kFwdBN - 1) / kFwdBN + KSPLIT - 1) / KSPLIT;  // same for both groups: one barrier each
+    fetch(grp * kFwdBN);
     stage(0);
     __syncthreads();
     int buf = 0;
-    for (int n0 = 0; n0 < n_end; n0 += kFwdBN, buf ^= 1) {
-        const bool more = n0 + kFwdBN < n_end;
-        if (more) fetch(n0 + kFwdBN);
+    for (int it = 0; it < n_iter; ++it, buf ^= 1) {
+        const int n0 = (it * KSPLIT + grp) * kFwdBN;
+        const bool more = n0 + KSPLIT * kFwdBN < n_end;
+        if (more) fetch(n0 + KSPLIT * kFwdBN);
 
-        if (n0 <= P + mw + 31) {  // otherwise every key of the tile is in this wave's future
+        if (n0 < n_end && n0 <= P + mw + 31) {  // otherwise every key of the tile is in this wave's future
             // S^T = K . Q^T : two 32-key blocks x this wave's 32 queries
             f32x16 s[2];
             {
@@ -271,6 +287,36 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
         __syncthreads();
     }
 
+    if (KSPLIT == 2) {
+        // group 1 hands its state over through the K tile area (all tile reads ended at the last barrier);
+        // word j of thread t sits at j * THREADS + t: consecutive lanes, consecutive words
+        static_assert(KSPLIT == 1 || sizeof(ks_all) >= sizeof(float) * THREADS * (2 + DB * 16), "hand-over area");
+        float* xch = reinterpret_cast<float*>(&ks_all[0][0][0]);
+        if (grp == 1) {
+            xch[0 * THREADS + tid] = m_run;
+            xch[1 * THREADS + tid] = l_run;
+            if (want_out) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) xch[(2 + db * 16 + r) * THREADS + tid] = o[db][r];
+            }
+        }
+        __syncthreads();
+        if (grp == 1) return;
+        const float m1 = xch[0 * THREADS + tid], l1 = xch[1 * THREADS + tid];
+        const float m_all = fmaxf(m_run, m1);  // group 0 has seen key 0: a real maximum
+        const float f0 = __builtin_amdgcn_exp2f(m_run - m_all), f1 = __builtin_amdgcn_exp2f(m1 - m_all);
+        l_run = l_run * f0 + l1 * f1;
+        m_run = m_all;
+        if (want_out) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    o[db][r] = o[db][r] * f0 + xch[(2 + db * 16 + r) * THREADS + tid] * f1;
+        }
+    }
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     if (m < Tq) {
         if (h == 0) lse[(size_t)bh * geo.q_rows + m] = (m_run + log2f(l_tot)) * kLn2;
@@ -296,8 +342,11 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_fwd_mfma_kernel(
 // exponentials of a step are issued between the matrix instructions of the NEXT step (the score block of a
 // step is kept "pending" for one step), so that the vector and transcendental work of one block runs while
 // the matrix pipe computes the following one.
-template <int D, int NB, bool PIPE, int MINW>
-__global__ __launch_bounds__(kMfmaThreads, MINW) void colsum_mfma_kernel(
+// QSPLIT = 2 (launches of one workgroup per compute unit or less): 8 waves in two groups of 4 that own the same
+// keys and take alternate query tiles, each group staging its own tiles; group 1's column sums are added to
+// group 0's through LDS at the end (always in that order).
+template <int D, int NB, bool PIPE, int MINW, int QSPLIT>
+__global__ __launch_bounds__(kMfmaThreads * QSPLIT, MINW) void colsum_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const float* __restrict__ lse,
     float* __restrict__ head_imp, ScoreGeom geo, float scale_log2e, int n_ktiles, int n_heads,
     const int32_t* __restrict__ seq_len, int H)
@@ -306,11 +355,16 @@ __global__ __launch_bounds__(kMfmaThreads, MINW) void colsum_mfma_kernel(
     constexpr int QP = D + 8;
     constexpr int KEYS_W = 32 * NB;                   // keys per wave
     constexpr int BN = (kMfmaThreads / kWave) * KEYS_W;  // keys per workgroup
-    __shared__ __align__(16) uint16_t qs[2][kColBM * QP];
-    __shared__ __align__(16) float lse2[2][kColBM];  // row log-sum-exp in base-2 units
+    __shared__ __align__(16) uint16_t qs_all[QSPLIT][2][kColBM * QP];
+    __shared__ __align__(16) float lse2_all[QSPLIT][2][kColBM];  // row log-sum-exp in base-2 units
+    __shared__ float col_xch[QSPLIT == 2 ? BN : 1];
 
-    const int tid = threadIdx.x, lane = tid % kWave;
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);  // scalar: conditions on it branch, not mask
+    const int tid = threadIdx.x % kMfmaThreads, lane = tid % kWave;  // tid: thread within its group
+    const int wave_wg = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int grp = wave_wg / (kMfmaThreads / kWave);   // scalar: which query tiles (tile number mod QSPLIT)
+    const int wave = wave_wg % (kMfmaThreads / kWave);  // scalar: which keys; conditions on it branch, not mask
+    uint16_t (*qs)[kColBM * QP] = qs_all[grp];
+    float (*lse2)[kColBM] = lse2_all[grp];
     const int c32 = lane % 32, h = lane / 32;
     const int item = xcd_contiguous_item(blockIdx.x, n_ktiles * n_heads);
     if (item >= n_ktiles * n_heads) return;
@@ -444,13 +498,15 @@ __global__ __launch_bounds__(kMfmaThreads, MINW) void colsum_mfma_kernel(
     };
 
     const int m_begin = (max(n0 - P, 0) / kColBM) * kColBM;  // first query tile that sees key n0 (query m sees n <= P + m)
-    fetch(m_begin);
+    const int n_iter = ((Tq - m_begin + kColBM - 1) / kColBM + QSPLIT - 1) / QSPLIT;  // same for both groups
+    fetch(m_begin + grp * kColBM);  // a tile beyond the sequence reads as zero queries with lse = +inf: no mass
     stage(0);
     __syncthreads();
     int buf = 0;
-    for (int m0 = m_begin; m0 < Tq; m0 += kColBM, buf ^= 1) {
-        const bool more = m0 + kColBM < Tq;
-        if (more) fetch(m0 + kColBM);
+    for (int it = 0; it < n_iter; ++it, buf ^= 1) {
+        const int m0 = m_begin + (it * QSPLIT + grp) * kColBM;
+        const bool more = m0 + QSPLIT * kColBM < Tq;
+        if (more) fetch(m0 + QSPLIT * kColBM);
 
         if (PIPE) {
             // a tile takes part as soon as one of its queries sees one of this wave's keys (wave-uniform); a
@@ -465,7 +521,7 @@ __global__ __launch_bounds__(kMfmaThreads, MINW) void colsum_mfma_kernel(
 #pragma unroll
             for (int st = 0; st < kColBM / 32; ++st) {
                 const int mq = m0 + st * 32;  // first query of this step
-                if (P + mq + 31 >= nw) {      // else no query of the step sees any of this wave's keys (wave-uniform)
+                if (mq < Tq && P + mq + 31 >= nw) {  // else no query of the step sees any of this wave's keys (wave-uniform)
                     // no pending block: this step's exponentials follow its own matrix instructions; other
                     // waves of the SIMD fill the matrix pipe meanwhile
                     bf16x8 qa[KB];
@@ -482,12 +538,26 @@ __global__ __launch_bounds__(kMfmaThreads, MINW) void colsum_mfma_kernel(
         __syncthreads();
     }
     if (PIPE) exp_masked(sB, lB, mq_pend);
+    float csum[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        float c = col[nb][0] + col[nb][1];
-        c += __shfl_xor(c, 32, kWave);
+        csum[nb] = col[nb][0] + col[nb][1];
+        csum[nb] += __shfl_xor(csum[nb], 32, kWave);
+    }
+    if (QSPLIT == 2) {
+        if (grp == 1 && h == 0) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) col_xch[wave * KEYS_W + nb * 32 + c32] = csum[nb];
+        }
+        __syncthreads();
+        if (grp == 1) return;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) csum[nb] += col_xch[wave * KEYS_W + nb * 32 + c32];
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
         const int n = nw + nb * 32 + c32;
-        if (h == 0 && n < L) head_imp[(size_t)bh * geo.imp_rows + n] = c;
+        if (h == 0 && n < L) head_imp[(size_t)bh * geo.imp_rows + n] = csum[nb];
     }
 }
 
@@ -503,26 +573,33 @@ static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, 
     // (measured crossover between 2048 and 3072 keys); 4-wave ones balance shorter prompts better
     int waves = forced_waves;
     if (waves != 4 && waves != 8) waves = (L >= 2560 && (long long)BH * ((Tq + 255) / 256) >= 512) ? 8 : 4;
+    const int qt128 = (Tq + 127) / 128;
     if (waves == 8)
-        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 8>), dim3(xcd_grid(((Tq + 255) / 256) * BH)), dim3(512), 0,
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 8, 1>), dim3(xcd_grid(((Tq + 255) / 256) * BH)), dim3(512), 0,
                            stream, q, k, v, out, lse, geo, sl, (Tq + 255) / 256, BH, seq_len, H);
+    else if (forced_waves == 0 && (long long)qt128 * BH <= kSplitMaxWorkgroups && L >= 4 * kFwdBN)
+        // a workgroup per compute unit or less: the launch lasts as long as its longest key loop
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 8, 2>), dim3(xcd_grid(qt128 * BH)), dim3(512), 0, stream, q, k,
+                           v, out, lse, geo, sl, qt128, BH, seq_len, H);
     else
-        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 4>), dim3(xcd_grid(((Tq + 127) / 128) * BH)), dim3(256), 0,
-                           stream, q, k, v, out, lse, geo, sl, (Tq + 127) / 128, BH, seq_len, H);
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 4, 1>), dim3(xcd_grid(qt128 * BH)), dim3(256), 0, stream, q, k,
+                           v, out, lse, geo, sl, qt128, BH, seq_len, H);
     int rc = status_from_hip(hipGetLastError());
     if (rc != EC_OK) return rc;
     // 64 keys per wave halve the LDS reads per matrix instruction; 32 keep twice as many workgroups for
     // shapes that would otherwise leave compute units idle
     const int kt256 = (L + 255) / 256, kt128 = (L + 127) / 128;
-#define EC_COLSUM(NB_, PIPE_, MINW_, KT_)                                                                        \
-    hipLaunchKernelGGL((colsum_mfma_kernel<D, NB_, PIPE_, MINW_>), dim3(xcd_grid(KT_ * BH)), dim3(kMfmaThreads), 0, \
-                       stream, q, k, lse, head_imp, geo, sl, KT_, BH, seq_len, H)
+#define EC_COLSUM(NB_, PIPE_, MINW_, KT_, QS_)                                                                   \
+    hipLaunchKernelGGL((colsum_mfma_kernel<D, NB_, PIPE_, MINW_, QS_>), dim3(xcd_grid(KT_ * BH)),                \
+                       dim3(kMfmaThreads * QS_), 0, stream, q, k, lse, head_imp, geo, sl, KT_, BH, seq_len, H)
     // measured (B4 H32 T8192 / B8 H32 T2048): 64 keys per wave with the pending-block pipeline 1165 / 223 us,
     // 32 keys per wave without it at four waves per SIMD 1272 / 202 us
     if ((long long)kt256 * BH >= 4096)
-        EC_COLSUM(2, true, 2, kt256);
+        EC_COLSUM(2, true, 2, kt256, 1);
+    else if ((long long)kt128 * BH <= kSplitMaxWorkgroups && Tq >= 4 * kColBM)
+        EC_COLSUM(1, false, 2, kt128, 2);  // the launch lasts as long as the first key tile's loop over the queries
     else
-        EC_COLSUM(1, false, 4, kt128);
+        EC_COLSUM(1, false, 4, kt128, 1);
 #undef EC_COLSUM
     return status_from_hip(hipGetLastError());
 }
