@@ -59,6 +59,27 @@ def test_tiny_config_full_layer():
         assert_close(score, ref["score"], cfg.dtype, "score")
 
 
+@pytest.mark.parametrize("D", [128, 64])
+@pytest.mark.parametrize("B,H,T", [
+    (1, 2, 255, ),    # one key tile short of the two-group launch shape
+    (1, 2, 256, ),    # its first length
+    (2, 16, 1024, ),  # 256 workgroups: the largest launch that takes it
+    (1, 33, 1024, ),  # 264 workgroups: the smallest that does not
+    (1, 3, 1100, ),   # odd number of key and of query tiles, ragged tail
+])
+def test_prefill_score_launch_shapes_of_short_prompts(D, B, H, T):
+    """bf16 launches of at most 256 workgroups run two wave groups per workgroup (alternate key tiles in the
+    forward pass, alternate query tiles in the column pass); both sides of every threshold are checked."""
+    cfg = syn.custom("t", H=H, D=D, B=B, T=T, dtype="bf16", cid=4000 + T + H)
+    q, k, v = syn.prompt_qkv(cfg)
+    ref = oracle.prefill_score(q, k, v, cfg.scale, 1)
+    out, lse, score = run_gpu_score(q, k, v, "bf16", cfg.scale, 1)
+    assert_close(out, ref["out"], "bf16", "out")
+    assert_close(lse, ref["lse"], "bf16", "lse")
+    assert_close(score, ref["score"], "bf16", "score")
+    np.testing.assert_allclose(score.sum(-1), T, rtol=1e-5)
+
+
 @pytest.mark.parametrize("B,G,Tq,P", [(2, 3, 300, 0), (1, 1, 37, 120), (3, 2, 1, 64), (1, 4, 5000, 700)])
 def test_importance_mean_metric(B, G, Tq, P):
     """Table 3d's "Mean" metric: the sums divided by the number of queries that see each row."""
