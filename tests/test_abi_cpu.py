@@ -166,3 +166,13 @@ def test_scale_must_be_finite_and_positive():
         assert lib.ec_decode_step(one, one, one, one, one, None, 1, 1, 1, 64, 8, 3, -1, 0, bad, 0, one, None, 0, None) == ec.EC_EINVAL
         assert lib.ec_decode_step_shaped(one, one, one, one, one, None, 1, 1, 1, 64, 8, 3, -1, 0, bad, 0, one, None, 0,
                                          0, 0, 0, None) == ec.EC_EINVAL
+
+
+def test_tune_tool_usage():
+    """The timing tool prints its usage for an unknown table and refuses to run without a GPU."""
+    import torch
+    from paper_2407_18121_amd import tune
+    assert tune.main(["tune"]) == 2
+    assert tune.main(["tune", "nonsense"]) == 2
+    if not torch.cuda.is_available():
+        assert tune.main(["tune", "decode"]) == 1
