@@ -570,9 +570,9 @@ static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, 
     const int Tq = geo.Tq, L = geo.L;
     const int BH = B * H;
     // 8-wave workgroups (256 queries) halve the LDS staging per flop, which pays once the key loop is long
-    // (measured crossover between 2048 and 3072 keys); 4-wave ones balance shorter prompts better
+    // (measured crossover between 2048 and 2304 keys); 4-wave ones balance shorter prompts better
     int waves = forced_waves;
-    if (waves != 4 && waves != 8) waves = (L >= 2560 && (long long)BH * ((Tq + 255) / 256) >= 512) ? 8 : 4;
+    if (waves != 4 && waves != 8) waves = (L >= 2176 && (long long)BH * ((Tq + 255) / 256) >= 512) ? 8 : 4;
     const int qt128 = (Tq + 127) / 128;
     if (waves == 8)
         hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, 8, 1>), dim3(xcd_grid(((Tq + 255) / 256) * BH)), dim3(512), 0,
