@@ -594,7 +594,7 @@ static int launch_mfma(const uint16_t* q, const uint16_t* k, const uint16_t* v, 
                        dim3(kMfmaThreads * QS_), 0, stream, q, k, lse, head_imp, geo, sl, KT_, BH, seq_len, H)
     // measured (B4 H32 T8192 / B8 H32 T2048): 64 keys per wave with the pending-block pipeline 1165 / 223 us,
     // 32 keys per wave without it at four waves per SIMD 1272 / 202 us
-    if ((long long)kt256 * BH >= 4096)
+    if ((long long)kt256 * BH >= 4096 || (L >= 6144 && (long long)kt256 * BH >= 1024))  // B2 H32 T8192: 1762 / 1802 us
         EC_COLSUM(2, true, 2, kt256, 1);
     else if ((long long)kt128 * BH <= kSplitMaxWorkgroups && Tq >= 4 * kColBM)
         EC_COLSUM(1, false, 2, kt128, 2);  // the launch lasts as long as the first key tile's loop over the queries
