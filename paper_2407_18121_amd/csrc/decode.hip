@@ -558,13 +558,26 @@ static int launch_decode(const void* q, const void* k_new, const void* v_new, vo
 #undef EC_DECODE_S
         return EC_EINVAL;
     }
-    if (waves <= 0) waves = (n_rows >= 96) ? 8 : 4;  // measured: 8 waves x 4 loads each beats 16 x 4 at every shape
+    // Width of a workgroup.  Measured (us per launch, 4 loads of K and of V in flight per lane; 2 / 4 / 8 / 16 waves):
+    //   B*H =   32,  640 rows: 20.6 / 12.4 /  9.8 / 10.8      B*H =  160,  640 rows: 22.4 / 14.6 / 12.4 / 13.1
+    //   B*H =  256,  576 rows: 23.8 / 16.1 / 15.5 / 16.1      B*H =  320,  256 rows: 13.1 / 11.7 / 12.8 / 15.4
+    //   B*H =  512,  870 rows: 40.6 / 39.7 / 42.0 / 45.5      B*H = 1536,  150 rows: 24.9 / 26.6 / 28.4 / 37.0
+    // With one workgroup per compute unit or less the wide workgroup streams fastest; once several workgroups
+    // share a compute unit, narrower ones (more of them resident, shorter tails) do.
+    if (waves <= 0) {
+        const long long bh = (long long)B * H;
+        waves = bh >= 1024 ? 2 : bh > 256 ? 4 : (n_rows >= 96 ? 8 : 4);
+    }
     if (unroll <= 0) unroll = 4;
 #define EC_DECODE_W(W_, U_)                                                                              \
     if (waves == W_ && unroll == U_)                                                                     \
         return launch_decode_w<DT, D, W_, U_>(q, k_new, v_new, k_cache, v_cache, pos, B, H, G, cap, cache_len, \
                                               evict_idx, new_pos, scale, out, len_b, evict_b, new_pos_b, stream);
+    EC_DECODE_W(2, 4)
+    EC_DECODE_W(2, 8)
     EC_DECODE_W(4, 4)
+    EC_DECODE_W(4, 6)
+    EC_DECODE_W(4, 8)
     EC_DECODE_W(8, 4)
     EC_DECODE_W(16, 4)
     EC_DECODE_W(16, 6)

@@ -76,6 +76,9 @@ def tune_decode():
         sets = 16 if name == "C5" else 32
         us, gbps = time_decode(B, H, D, N, 0, 0, 1, sets)
         print(f"decode {name} B{B} H{H} rows {N}: one launch (library's choice) {us:7.2f} us {gbps:7.0f} GB/s", flush=True)
+        for waves, unroll in ((2, 4), (2, 8), (4, 4), (4, 6), (4, 8), (4, 12), (8, 4), (8, 8), (16, 4)):
+            us, gbps = time_decode(B, H, D, N, waves, unroll, 1, sets)
+            print(f"decode {name}:   one launch, {waves:2d} waves x {unroll:2d} loads in flight {us:7.2f} us {gbps:7.0f} GB/s", flush=True)
         best = None
         for splits in (2, 3, 4, 6, 8, 12, 16):
             if B * H * splits > 4096 or N // splits < 32:

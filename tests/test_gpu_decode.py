@@ -70,13 +70,22 @@ def test_decode_step_shapes(dtype, D, B, H, G, cap, cache_len, evict_idx):
     _case(dtype, D, B, H, G, cap, cache_len, evict_idx, seed=cache_len * 7 + D)
 
 
-@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("waves", [2, 4, 8, 16])
 def test_decode_step_workgroup_widths(waves):
     shape = (waves, 0, 1)   # one workgroup per (batch, head), explicit width
     _case("bf16", 128, 2, 3, 1, 900, 777, 777 - 25, seed=waves, shape=shape)
     _case("f32", 64, 1, 4, 4, 900, 130, 3, seed=waves + 100, shape=shape)     # more than one tile moves
     _case("bf16", 64, 1, 2, 2, 900, 511, 511, seed=waves + 200, shape=shape)  # victim = new row, full tiles
     _case("f32", 128, 1, 2, 1, 900, 512, 1, seed=waves + 300, shape=shape)
+
+
+@pytest.mark.parametrize("waves,unroll", [(2, 4), (2, 8), (4, 6), (4, 8), (4, 12), (8, 8), (8, 12), (16, 6)])
+def test_decode_step_loads_in_flight(waves, unroll):
+    """Every (width, loads in flight) pair the fused kernel is built for, victim inside and outside the last tile."""
+    shape = (waves, unroll, 1)
+    _case("bf16", 128, 2, 3, 1, 900, 777, 777 - 25, seed=10 * waves + unroll, shape=shape)
+    _case("f32", 128, 1, 2, 1, 900, 512, 512 - 25, seed=10 * waves + unroll + 1, shape=shape)
+    _case("bf16", 64, 1, 2, 2, 300, 130, 3, seed=10 * waves + unroll + 2, shape=shape)
 
 
 @pytest.mark.parametrize("splits", [2, 3, 8, 16])
